@@ -1,0 +1,70 @@
+// Internal declarations shared by the translation units of libqesgd (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qesgd.h"
+
+namespace qesgd {
+
+// Coordinates handled by one lane per chunk, lanes per wavefront, and the
+// resulting wave chunk: 64 lanes x 8 consecutive coordinates.
+constexpr uint32_t kLaneElems = 8;
+constexpr uint32_t kWaveSize = 64;
+constexpr uint32_t kChunk = kLaneElems * kWaveSize;   // 512
+
+// Largest zero-padded bucket whose scale is found in the same pass that
+// quantises it (16 waves x 4 chunks x 512 coordinates held in registers).
+constexpr uint64_t kMaxSinglePassBucket = 32768;
+// Tile of the partial-sum pass used for larger buckets.
+constexpr uint64_t kPartialTile = 4096;
+
+struct Shape {
+    uint64_t d;
+    uint32_t s;
+    uint32_t m;          // level bits
+    uint64_t B;          // effective bucket = min(bucket, d)
+    uint64_t nb;         // buckets
+    uint64_t N;          // B zero-padded to a power of two, at least 8
+    uint32_t log2N;
+    qesgd_layout lay;
+};
+
+// Validates (d, s, bucket) and fills the shape; returns QESGD_OK or an error.
+int make_shape(uint64_t d, uint32_t s, uint64_t bucket, Shape* out);
+
+struct QuantizeArgs {
+    const float* x;
+    uint64_t x_stride;       // floats between workers
+    const float* center;     // nullable
+    uint32_t norm_kind;
+    uint64_t seed;
+    uint32_t round;
+    uint32_t worker0;        // worker id of slab row 0
+    uint32_t K;              // rows
+    unsigned char* packed;
+    uint64_t packed_stride;  // bytes between workers
+    float* workspace;        // two-pass path only
+    hipStream_t stream;
+};
+
+struct AggregateArgs {
+    const unsigned char* packed;
+    uint64_t packed_stride;
+    uint32_t K;
+    const float* w_snap;     // nullable: no update
+    float* zbar_out;         // nullable
+    float* u_out;            // nullable iff w_snap is
+    float* zsum;             // nullable
+    hipStream_t stream;
+};
+
+int launch_quantize(const Shape& sh, const QuantizeArgs& a);
+int launch_aggregate(const Shape& sh, const AggregateArgs& a);
+int launch_apply_update(const float* w, const float* zbar, float* u, float* zsum, uint64_t d,
+                        hipStream_t stream);
+
+void set_last_hip_error(int e);
+
+}  // namespace qesgd

@@ -1,0 +1,138 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports what the
+header declares, computes the packed layout, and rejects bad arguments before any HIP call."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "qesgd.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1901_03040_amd import binding
+    binding.lib()
+    return binding
+
+
+def test_exports_every_declared_symbol(B):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(qesgd_[a-z_0-9]+)\s*\(", text))
+    assert {"qesgd_quantize_pack", "qesgd_unpack_aggregate", "qesgd_apply_update"} <= names
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(B.lib(), n), n
+    assert B.qesgd_abi_version() == 1
+    assert B.qesgd_last_hip_error() == 0
+
+
+def test_error_strings(B):
+    for code in range(0, -11, -1):
+        assert B.strerror(code) and "unknown" not in B.strerror(code)
+    assert "unknown" in B.strerror(-99)
+
+
+@pytest.mark.parametrize("d,s,bucket,nb,m", [
+    (16_384, 4, 16_384, 1, 2), (1_048_576, 16, 512, 2048, 4), (11_173_962, 4, 2048, 5457, 2),
+    (25_557_032, 256, 8192, 3120, 8), (138_357_544, 2, 4096, 33_779, 1), (1000, 65536, 96, 11, 16),
+    (5, 2, 4096, 1, 1)])
+def test_layout(B, d, s, bucket, nb, m):
+    lay = B.qesgd_layout_query(d, s, bucket)
+    assert (lay.n_buckets, lay.level_bits) == (nb, m)
+    assert lay.sign_words == (d + 31) // 32 and lay.level_words == (d * m + 31) // 32
+    assert lay.payload_bytes == 4 * (nb + lay.sign_words + lay.level_words)
+    offs = [lay.norms_off, lay.signs_off, lay.levels_off, lay.bytes_per_worker]
+    assert all(o % 256 == 0 for o in offs) and offs == sorted(offs)
+    assert lay.signs_off >= 4 * nb and lay.levels_off - lay.signs_off >= 4 * lay.sign_words
+    assert lay.bytes_per_worker - lay.levels_off >= 4 * lay.level_words
+    assert lay.bytes_per_worker - lay.payload_bytes < 3 * 256
+
+
+def test_payload_matches_table(B):
+    """Packed bytes per worker of the five configurations (4*nb + 4*ceil(d/32) + 4*ceil(d*m/32))."""
+    want = {(16_384, 4, 16_384): 6_148, (1_048_576, 16, 512): 663_552, (11_173_962, 4, 2048): 4_212_068,
+            (25_557_032, 256, 8192): 28_764_144, (138_357_544, 2, 4096): 34_724_508}
+    for (d, s, b), p in want.items():
+        assert B.qesgd_layout_query(d, s, b).payload_bytes == p
+
+
+def test_layout_errors(B):
+    for args, code in [((0, 4, 32), B.ERR_DIM), ((1 << 40, 4, 32), B.ERR_DIM), ((100, 3, 32), B.ERR_LEVELS),
+                       ((100, 1, 32), B.ERR_LEVELS), ((100, 4, 0), B.ERR_BUCKET), ((100, 4, 48), B.ERR_BUCKET)]:
+        with pytest.raises(B.QesgdError) as e:
+            B.qesgd_layout_query(*args)
+        assert e.value.code == code
+    B.qesgd_layout_query(100, 4, 100)      # bucket >= d needs no multiple of 32
+    B.qesgd_layout_query(100, 4, 1000)
+    assert B.lib().qesgd_layout_query(100, 4, 32, None) == B.ERR_NULL
+
+
+def test_workspace_bytes(B):
+    assert B.qesgd_workspace_bytes(138_357_544, 2, 4096, 8) == 0
+    assert B.qesgd_workspace_bytes(1 << 20, 4, 32768, 8) == 0
+    # one bucket of 2^20 coordinates: 2^20 / 4096 partial sums per worker
+    assert B.qesgd_workspace_bytes(1 << 20, 4, 1 << 20, 3) == 3 * 256 * 4
+    assert B.qesgd_workspace_bytes(100_000, 4, 100_000, 1) == (131_072 // 4096) * 4
+    assert B.qesgd_workspace_bytes(0, 4, 32, 1) == 0
+
+
+def _rc_quant(B, x=0x10000, center=None, d=4096, s=4, bucket=512, kind=0, packed=0x20000,
+              ws=None, ws_bytes=0):
+    return B.lib().qesgd_quantize_pack(x, center, d, s, bucket, kind, 1, 0, 0, packed, ws, ws_bytes, None)
+
+
+def _rc_quant_b(B, x=0x10000, stride=4096, d=4096, s=4, bucket=512, K=2, packed=0x20000, pstride=1 << 20):
+    return B.lib().qesgd_quantize_pack_batched(x, stride, None, d, s, bucket, 0, 1, 0, K, packed, pstride,
+                                               None, 0, None)
+
+
+def test_quantize_argument_errors(B):
+    """Fake device addresses: every call below must be rejected before a launch is attempted."""
+    assert _rc_quant(B, x=None) == B.ERR_NULL
+    assert _rc_quant(B, packed=None) == B.ERR_NULL
+    assert _rc_quant(B, d=0) == B.ERR_DIM
+    assert _rc_quant(B, s=3) == B.ERR_LEVELS
+    assert _rc_quant(B, bucket=0) == B.ERR_BUCKET
+    assert _rc_quant(B, bucket=100) == B.ERR_BUCKET
+    assert _rc_quant(B, kind=2) == B.ERR_NORM_KIND
+    assert _rc_quant(B, x=0x10004) == B.ERR_ALIGN
+    assert _rc_quant(B, center=0x10008) == B.ERR_ALIGN
+    assert _rc_quant(B, packed=0x20010) == B.ERR_ALIGN
+    assert _rc_quant(B, d=100_000, bucket=100_000) == B.ERR_WORKSPACE
+    assert _rc_quant(B, d=100_000, bucket=100_000, ws=0x30000, ws_bytes=64) == B.ERR_WORKSPACE
+    assert _rc_quant_b(B, K=0) == B.ERR_WORKERS
+    assert _rc_quant_b(B, K=65) == B.ERR_WORKERS
+    assert _rc_quant_b(B, stride=4000) == B.ERR_STRIDE
+    assert _rc_quant_b(B, stride=4098) == B.ERR_STRIDE
+    assert _rc_quant_b(B, pstride=256) == B.ERR_STRIDE
+    assert _rc_quant_b(B, pstride=(1 << 20) + 16) == B.ERR_STRIDE
+
+
+def test_aggregate_argument_errors(B):
+    L = B.lib()
+    pk, z, w, u = 0x20000, 0x30000, 0x40000, 0x50000
+    assert L.qesgd_unpack_aggregate(None, 1 << 20, 2, 4096, 4, 512, z, None) == B.ERR_NULL
+    assert L.qesgd_unpack_aggregate(pk, 1 << 20, 2, 4096, 4, 512, None, None) == B.ERR_NULL
+    assert L.qesgd_unpack_aggregate(pk, 1 << 20, 0, 4096, 4, 512, z, None) == B.ERR_WORKERS
+    assert L.qesgd_unpack_aggregate(pk, 1 << 20, 2, 4096, 5, 512, z, None) == B.ERR_LEVELS
+    assert L.qesgd_unpack_aggregate(pk, 128, 2, 4096, 4, 512, z, None) == B.ERR_STRIDE
+    assert L.qesgd_unpack_aggregate(pk, 1 << 20, 2, 4096, 4, 512, z + 4, None) == B.ERR_ALIGN
+    assert L.qesgd_unpack_aggregate(pk + 64, 1 << 20, 2, 4096, 4, 512, z, None) == B.ERR_ALIGN
+    assert L.qesgd_unpack_aggregate_update(pk, 1 << 20, 2, 4096, 4, 512, None, z, u, None, None) == B.ERR_NULL
+    assert L.qesgd_unpack_aggregate_update(pk, 1 << 20, 2, 4096, 4, 512, w, z, None, None, None) == B.ERR_NULL
+    assert L.qesgd_unpack_aggregate_update(pk, 1 << 20, 2, 0, 4, 512, w, z, u, None, None) == B.ERR_DIM
+    assert L.qesgd_unpack_aggregate_update(pk, 1 << 20, 2, 4096, 4, 512, w, z, u, 0x60008, None) == B.ERR_ALIGN
+    assert L.qesgd_apply_update(None, z, u, None, 10, None) == B.ERR_NULL
+    assert L.qesgd_apply_update(w, z, u, None, 0, None) == B.ERR_DIM
+    assert L.qesgd_apply_update(w, z, u + 8, None, 10, None) == B.ERR_ALIGN
+
+
+def test_missing_library_is_loud(monkeypatch):
+    from paper_1901_03040_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libqesgd.so")
+    with pytest.raises(RuntimeError, match="not found"):
+        binding.qesgd_layout_query(10, 4, 32)

@@ -1,0 +1,343 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: norms, sign words and level words bit-exact; zbar / u / zsum within 1e-6 of the oracle
+(max |difference| / max |oracle|), which they in fact meet bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1901_03040_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.lib()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def S():
+    from paper_1901_03040_amd import synth
+    return synth
+
+
+def host_planes(B, packed_row, lay):
+    n, s, l = B.planes(packed_row, lay)
+    return (n.cpu().numpy().copy(), s.cpu().numpy().view(np.uint32).copy(),
+            l.cpu().numpy().view(np.uint32).copy())
+
+
+def gpu_quantize(B, x, s, bucket, seed, rnd, worker, center=None, norm_kind=0, poison=True):
+    d = x.numel()
+    lay = B.qesgd_layout_query(d, s, bucket)
+    packed = B.alloc_packed(lay, 1)
+    if poison:
+        packed.fill_(0xA5)
+    wsb = B.qesgd_workspace_bytes(d, s, bucket, 1)
+    ws = torch.empty(max(wsb, 4) // 4, dtype=torch.float32, device="cuda") if wsb else None
+    B.qesgd_quantize_pack(x, center, d, s, bucket, norm_kind, seed, rnd, worker, packed, ws)
+    torch.cuda.synchronize()
+    return lay, packed
+
+
+def assert_codes_equal(oracle, B, x_host, s, bucket, seed, rnd, worker, lay, packed_row,
+                       center_host=None, norm_kind=0):
+    norms, sw, lw = host_planes(B, packed_row, lay)
+    on, osw, olw = oracle.quantize_pack(x_host, s, bucket, seed, rnd, worker, center=center_host,
+                                        norm_kind=norm_kind)
+    assert np.array_equal(norms.view(np.uint32), on.view(np.uint32)), "bucket scales differ"
+    bad = np.nonzero(sw != osw)[0]
+    assert bad.size == 0, f"sign words differ at {bad[:5]}"
+    bad = np.nonzero(lw != olw)[0]
+    assert bad.size == 0, f"level words differ at {bad[:5]} of {lw.size}"
+
+
+def rel_err(got, want):
+    denom = float(np.max(np.abs(want))) or 1.0
+    return float(np.max(np.abs(got.astype(np.float64) - want.astype(np.float64)))) / denom
+
+
+# ---------------------------------------------------------------------------
+# quantize + pack
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("s", [2, 4, 16, 256, 65536])
+@pytest.mark.parametrize("d,bucket", [
+    (20_000, 512), (20_010, 2048), (33_001, 4096), (70_003, 8192), (70_003, 16_384),
+    (100_007, 32_768), (5_000, 32), (5_003, 64), (9_999, 96), (9_000, 1_000_000), (40_000, 40_000),
+    (100_000, 100_000), (300_001, 131_072 * 2)])
+def test_quantize_pack_matches_oracle(oracle, B, s, d, bucket):
+    g = torch.Generator(device="cpu").manual_seed(d * 31 + s)
+    x = (torch.randn(d, generator=g) * 1e-3).to(torch.float32)
+    seed, rnd, worker = 0xC0FFEE0000 + s, 3, 5
+    lay, packed = gpu_quantize(B, x.cuda(), s, bucket, seed, rnd, worker)
+    assert_codes_equal(oracle, B, x.numpy(), s, bucket, seed, rnd, worker, lay, packed[0])
+
+
+@pytest.mark.parametrize("d", [1, 2, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 255, 511, 512, 513, 4095, 4097])
+@pytest.mark.parametrize("s", [2, 16, 256])
+def test_tiny_and_ragged_sizes(oracle, B, s, d):
+    g = torch.Generator(device="cpu").manual_seed(d)
+    x = (torch.randn(d, generator=g) * 0.1).to(torch.float32)
+    for bucket in {d, 32, 1 << 20}:
+        lay, packed = gpu_quantize(B, x.cuda(), s, bucket, 11, 0, 0)
+        assert_codes_equal(oracle, B, x.numpy(), s, bucket, 11, 0, 0, lay, packed[0])
+
+
+@pytest.mark.parametrize("norm_kind", [0, 1])
+@pytest.mark.parametrize("d,bucket,s", [(50_001, 512, 16), (50_001, 8192, 4), (70_000, 70_000, 256), (5_000, 96, 2)])
+def test_center_and_max_norm(oracle, B, norm_kind, d, bucket, s):
+    g = torch.Generator(device="cpu").manual_seed(7)
+    w = torch.randn(d, generator=g).to(torch.float32)
+    x = w + (torch.randn(d, generator=g) * 1e-3).to(torch.float32)
+    lay, packed = gpu_quantize(B, x.cuda(), s, bucket, 5, 1, 2, center=w.cuda(), norm_kind=norm_kind)
+    assert_codes_equal(oracle, B, x.numpy(), s, bucket, 5, 1, 2, lay, packed[0], center_host=w.numpy(),
+                       norm_kind=norm_kind)
+
+
+def test_degenerate_inputs(oracle, B):
+    d, bucket = 10_000, 512
+    for s in (2, 256):
+        x = torch.zeros(d)
+        lay, packed = gpu_quantize(B, x.cuda(), s, bucket, 1, 0, 0)
+        norms, sw, lw = host_planes(B, packed[0], lay)
+        assert not norms.any() and not sw.any() and not lw.any()
+        # one-hot buckets, negative zeros, a bucket of denormals, huge and tiny magnitudes
+        x = torch.zeros(d)
+        x[100] = -0.125
+        x[600] = -0.0
+        x[1024:1536] = 1e-41
+        x[2048:2560] = 3e17
+        x[3072:3584] = torch.linspace(-1e-30, 1e-30, 512)
+        x[4096] = 1e-45
+        lay, packed = gpu_quantize(B, x.cuda(), s, bucket, 1, 0, 0)
+        assert_codes_equal(oracle, B, x.numpy(), s, bucket, 1, 0, 0, lay, packed[0])
+
+
+def test_padding_bits_zero_and_gaps_untouched(oracle, B):
+    d, s, bucket = 1001, 4, 96
+    x = torch.full((d,), -1.0)
+    lay, packed = gpu_quantize(B, x.cuda(), s, bucket, 1, 0, 0)
+    norms, sw, lw = host_planes(B, packed[0], lay)
+    assert sw[-1] >> (d % 32) == 0 and (sw[:-1] == 0xFFFFFFFF).all()
+    assert lw[-1] >> ((2 * d) % 32) == 0
+    raw = packed[0].cpu().numpy()
+    gap = np.ones(raw.size, bool)
+    for off, n in [(lay.norms_off, 4 * lay.n_buckets), (lay.signs_off, 4 * lay.sign_words),
+                   (lay.levels_off, 4 * lay.level_words)]:
+        gap[off:off + n] = False
+    assert (raw[gap] == 0xA5).all()             # bytes between the planes are never written
+
+
+def test_levels_within_range_and_distribution(oracle, B):
+    """Properties that hold at any size: level <= s-1, dequantised value within one step of v,
+    and the sample mean over many coordinates is unbiased."""
+    d, s, bucket = 1 << 20, 16, 512
+    g = torch.Generator(device="cpu").manual_seed(1)
+    x = (torch.randn(d, generator=g) * 1e-3).to(torch.float32)
+    lay, packed = gpu_quantize(B, x.cuda(), s, bucket, 77, 0, 0)
+    norms, sw, lw = host_planes(B, packed[0], lay)
+    level, sign = oracle.unpack(sw, lw, d, s)
+    assert level.max() <= s - 1
+    step = np.repeat(norms.astype(np.float64) / (s - 1), bucket)[:d]
+    q = np.where(sign == 1, -1.0, 1.0) * level * step
+    xd = x.numpy().astype(np.float64)
+    assert np.all(np.abs(q - xd) <= step * (1 + 1e-6))
+    assert abs(float((q - xd).sum())) <= 5 * float(np.sqrt((step ** 2 / 4).sum()))
+
+
+def test_batched_equals_single_calls_and_streams_are_keyed(oracle, B, S):
+    cfg = S.by_name("cfg2").scaled(d=50_000, K=5)
+    slab = S.worker_slab(cfg, "cuda")
+    stride = slab.stride(0)
+    lay = B.qesgd_layout_query(cfg.d, cfg.s, cfg.bucket)
+    packed = B.alloc_packed(lay, cfg.K)
+    packed.fill_(0)
+    B.qesgd_quantize_pack_batched(slab, stride, None, cfg.d, cfg.s, cfg.bucket, 0, 9, 4, cfg.K, packed,
+                                  packed.stride(0))
+    torch.cuda.synchronize()
+    for k in range(cfg.K):
+        single = B.alloc_packed(lay, 1)
+        single.fill_(0)
+        B.qesgd_quantize_pack(slab[k], None, cfg.d, cfg.s, cfg.bucket, 0, 9, 4, k, single)
+        torch.cuda.synchronize()
+        assert torch.equal(single[0], packed[k])
+        assert_codes_equal(oracle, B, slab[k, :cfg.d].cpu().numpy(), cfg.s, cfg.bucket, 9, 4, k, lay, packed[k])
+    # same triple -> same bytes; another round -> other codes
+    again = B.alloc_packed(lay, cfg.K)
+    again.fill_(0)
+    B.qesgd_quantize_pack_batched(slab, stride, None, cfg.d, cfg.s, cfg.bucket, 0, 9, 4, cfg.K, again,
+                                  again.stride(0))
+    other = B.alloc_packed(lay, cfg.K)
+    other.fill_(0)
+    B.qesgd_quantize_pack_batched(slab, stride, None, cfg.d, cfg.s, cfg.bucket, 0, 9, 5, cfg.K, other,
+                                  other.stride(0))
+    torch.cuda.synchronize()
+    assert torch.equal(again, packed) and not torch.equal(other, packed)
+
+
+@pytest.mark.parametrize("name,d", [("cfg1", 16_384), ("cfg2", 40_000), ("cfg3", 41_034), ("cfg4", 70_008),
+                                    ("cfg5", 61_000)])
+def test_config_distributions_small(oracle, B, S, name, d):
+    """Each configuration's value distribution at a size the oracle finishes in seconds."""
+    cfg = S.by_name(name).scaled(d=d, K=2)
+    slab = S.worker_slab(cfg, "cuda")
+    lay = B.qesgd_layout_query(cfg.d, cfg.s, cfg.bucket)
+    packed = B.alloc_packed(lay, cfg.K)
+    B.qesgd_quantize_pack_batched(slab, slab.stride(0), None, cfg.d, cfg.s, cfg.bucket, 0, cfg.seed, 0, cfg.K,
+                                  packed, packed.stride(0))
+    torch.cuda.synchronize()
+    for k in range(cfg.K):
+        assert_codes_equal(oracle, B, slab[k, :cfg.d].cpu().numpy(), cfg.s, cfg.bucket, cfg.seed, 0, k, lay, packed[k])
+
+
+# ---------------------------------------------------------------------------
+# unpack + aggregate + update
+# ---------------------------------------------------------------------------
+def random_packed(B, S, d, s, bucket, K, seed):
+    lay = B.qesgd_layout_query(d, s, bucket)
+    packed = B.alloc_packed(lay, K)
+    packed.fill_(0x5A)
+    for k in range(K):
+        n, sg, lv = B.planes(packed[k], lay)
+        n.copy_(S.random_norms(lay.n_buckets, seed, k, "cuda"))
+        sg.copy_(S.random_packed_words(lay.sign_words, seed, 2 * k, "cuda"))
+        lv.copy_(S.random_packed_words(lay.level_words, seed, 2 * k + 1, "cuda"))
+    return lay, packed
+
+
+def oracle_planes(B, packed, lay, K):
+    ns, ss, ls = [], [], []
+    for k in range(K):
+        n, s, l = host_planes(B, packed[k], lay)
+        ns.append(n), ss.append(s), ls.append(l)
+    return np.stack(ns), np.stack(ss), np.stack(ls)
+
+
+@pytest.mark.parametrize("s,K", [(2, 8), (4, 3), (16, 8), (256, 16), (65536, 5), (4, 1), (16, 64)])
+@pytest.mark.parametrize("d,bucket", [(30_000, 512), (30_005, 4096), (9_999, 96), (1001, 5000), (7, 32)])
+def test_unpack_aggregate_update_matches_oracle(oracle, B, S, s, K, d, bucket):
+    lay, packed = random_packed(B, S, d, s, bucket, K, seed=s + K)
+    g = torch.Generator(device="cpu").manual_seed(d)
+    w = torch.randn(d, generator=g)
+    zsum0 = torch.randn(d, generator=g) * 1e-2
+    zbar = torch.full((d,), float("nan"), device="cuda")
+    u = torch.full((d,), float("nan"), device="cuda")
+    zsum = zsum0.cuda()
+    B.qesgd_unpack_aggregate_update(packed, packed.stride(0), K, d, s, bucket, w.cuda(), zbar, u, zsum)
+    torch.cuda.synchronize()
+    norms, sw, lw = oracle_planes(B, packed, lay, K)
+    ozbar = oracle.unpack_aggregate(norms, sw, lw, d, s, bucket)
+    ou, ozsum = oracle.apply_update(w.numpy(), ozbar, zsum0.numpy())
+    for got, want, what in [(zbar, ozbar, "zbar"), (u, ou, "u"), (zsum, ozsum, "zsum")]:
+        got = got.cpu().numpy()
+        assert rel_err(got, want) <= TOL, what
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), f"{what} not bit-exact"
+    # the two-call form gives the same bits, and aliasing u onto w is allowed
+    zbar2 = torch.empty(d, device="cuda")
+    B.qesgd_unpack_aggregate(packed, packed.stride(0), K, d, s, bucket, zbar2)
+    wu = w.cuda()
+    zsum2 = zsum0.cuda()
+    B.qesgd_apply_update(wu, zbar2, wu, zsum2, d)
+    torch.cuda.synchronize()
+    assert torch.equal(zbar2, zbar) and torch.equal(wu, u) and torch.equal(zsum2, zsum)
+    # optional outputs
+    u3 = torch.empty(d, device="cuda")
+    B.qesgd_unpack_aggregate_update(packed, packed.stride(0), K, d, s, bucket, w.cuda(), None, u3, None)
+    torch.cuda.synchronize()
+    assert torch.equal(u3, u)
+
+
+def test_full_round_small(oracle, B, S):
+    """quantize -> aggregate -> update for several rounds, each side on its own intermediates."""
+    cfg = S.by_name("cfg3").scaled(d=41_034, K=4)
+    slab = S.worker_slab(cfg, "cuda")
+    w = S.snapshot(cfg, "cuda")
+    host = slab[:, :cfg.d].cpu().numpy()
+    lay = B.qesgd_layout_query(cfg.d, cfg.s, cfg.bucket)
+    packed = B.alloc_packed(lay, cfg.K)
+    zbar = torch.empty(cfg.d, device="cuda")
+    u = torch.empty(cfg.d, device="cuda")
+    zsum = torch.zeros(cfg.d, device="cuda")
+    ozsum = np.zeros(cfg.d, np.float32)
+    rot = torch.empty_like(slab)
+    for rnd in range(3):
+        order = [(k + rnd) % cfg.K for k in range(cfg.K)]
+        rot.copy_(slab[order])
+        B.qesgd_quantize_pack_batched(rot, rot.stride(0), None, cfg.d, cfg.s, cfg.bucket, 0, cfg.seed, rnd,
+                                      cfg.K, packed, packed.stride(0))
+        B.qesgd_unpack_aggregate_update(packed, packed.stride(0), cfg.K, cfg.d, cfg.s, cfg.bucket, w, zbar, u, zsum)
+        torch.cuda.synchronize()
+        op = [oracle.quantize_pack(host[order[k]], cfg.s, cfg.bucket, cfg.seed, rnd, k) for k in range(cfg.K)]
+        oz = oracle.unpack_aggregate(np.stack([p[0] for p in op]), np.stack([p[1] for p in op]),
+                                     np.stack([p[2] for p in op]), cfg.d, cfg.s, cfg.bucket)
+        ou, ozsum = oracle.apply_update(w.cpu().numpy(), oz, ozsum)
+        assert rel_err(zbar.cpu().numpy(), oz) <= TOL
+        assert rel_err(u.cpu().numpy(), ou) <= TOL
+        assert rel_err(zsum.cpu().numpy(), ozsum) <= TOL
+        assert np.array_equal(u.cpu().numpy(), ou)
+
+
+# ---------------------------------------------------------------------------
+# Full-size configurations in the benchmark's launch configuration: sampled buckets /
+# ranges against the oracle, whole-output properties.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+def test_full_size_config_sampled(oracle, B, S, name):
+    cfg = S.by_name(name)
+    d, K, s, bucket = cfg.d, cfg.K, cfg.s, cfg.bucket
+    slab = S.worker_slab(cfg, "cuda")
+    lay = B.qesgd_layout_query(d, s, bucket)
+    packed = B.alloc_packed(lay, K)
+    packed.fill_(0)
+    rnd = 1
+    B.qesgd_quantize_pack_batched(slab, slab.stride(0), None, d, s, bucket, 0, cfg.seed, rnd, K, packed,
+                                  packed.stride(0))
+    torch.cuda.synchronize()
+    nb, _, _, N, m = oracle.shape(d, s, bucket)
+    Bk = min(bucket, d)
+    rng = np.random.default_rng(cfg.seed)
+    buckets = sorted({0, 1 % nb, nb - 1, nb - 2 if nb > 1 else 0, *rng.integers(0, nb, size=6).tolist()})
+    for k in sorted({0, K - 1, int(rng.integers(0, K))}):
+        norms, sg, lv = B.planes(packed[k], lay)
+        for b in buckets:
+            i0, i1 = b * Bk, min((b + 1) * Bk, d)
+            v = slab[k, i0:i1].cpu().numpy()
+            onorm, olevel, osign = oracle.quantize_bucket(v, N, i0, s, cfg.seed, rnd, k)
+            assert np.float32(onorm).tobytes() == np.float32(norms[b].item()).tobytes(), (k, b)
+            # the words that hold this bucket (bucket starts are multiples of 32 coordinates)
+            w0, w1 = i0 // 32, (i1 + 31) // 32
+            sw = sg[w0:w1].cpu().numpy().view(np.uint32)
+            l0, l1 = (i0 * m) // 32, (i1 * m + 31) // 32
+            lw = lv[l0:l1].cpu().numpy().view(np.uint32)
+            osw, olw = oracle.pack(olevel, osign, s)
+            assert np.array_equal(sw, osw), (k, b)
+            assert np.array_equal(lw, olw), (k, b)
+    # aggregate + update at the same shape, on seeded random code planes (any bit pattern is a
+    # valid code): sampled ranges against the oracle
+    del slab, packed
+    torch.cuda.empty_cache()
+    lay, packed = random_packed(B, S, d, s, bucket, K, seed=cfg.seed)
+    w = S.snapshot(cfg, "cuda")
+    zbar = torch.empty(d, device="cuda")
+    u = torch.empty(d, device="cuda")
+    zsum = torch.zeros(d, device="cuda")
+    B.qesgd_unpack_aggregate_update(packed, packed.stride(0), K, d, s, bucket, w, zbar, u, zsum)
+    torch.cuda.synchronize()
+    hn, hs, hl = oracle_planes(B, packed, lay, K)
+    starts = sorted({0, max(0, d - 5000), *[int(x) for x in rng.integers(0, max(1, d - 5000), size=4)]})
+    for a in starts:
+        e = min(d, a + 5000)
+        oz = oracle.unpack_aggregate(hn, hs, hl, d, s, bucket, a, e)
+        ou, ozs = oracle.apply_update(w[a:e].cpu().numpy(), oz, np.zeros(e - a, np.float32))
+        assert rel_err(zbar[a:e].cpu().numpy(), oz) <= TOL, a
+        assert np.array_equal(zbar[a:e].cpu().numpy(), oz), a
+        assert np.array_equal(u[a:e].cpu().numpy(), ou), a
+        assert np.array_equal(zsum[a:e].cpu().numpy(), ozs), a
+    # whole-output properties: zsum == zbar after one round from zero, u - w == zbar up to rounding
+    assert torch.equal(zsum, zbar)
+    assert float((u - w - zbar).abs().max()) <= float(w.abs().max() + zbar.abs().max()) * 2.0 ** -23
