@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the QESGD hot path on one MI355X.
+
+A step is one synchronous round over one batch of synthetic input, already resident in HBM:
+  1. qesgd_quantize_pack_batched   K simulated workers' vectors -> K packed blocks
+  2. qesgd_unpack_aggregate_update K packed blocks + w_t, zsum  -> zbar, u, zsum
+Reported: whole-step throughput in GB/s of algorithmic bytes (K*(4d+P) + K*P + 20d per step,
+P = packed bytes per worker), per-phase GB/s and parameters/s, the roofline of the dominant
+kernel from HIP events on the launch stream, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+
+
+def algorithmic_bytes(cfg, lay):
+    P = lay.payload_bytes
+    q = cfg.K * (4 * cfg.d + P)          # read K vectors, write K packed payloads
+    uau = cfg.K * P + 20 * cfg.d         # read K payloads + w + zsum, write zbar + u + zsum
+    return q, uau
+
+
+def cpu_baseline(cfg, slab, w, lay, budget_elems=1 << 26):
+    """The oracle as it stands, one host thread, on a bucket-aligned prefix of the same workload."""
+    import numpy as np
+    from oracle import qesgd_oracle as oracle
+    B = min(cfg.bucket, cfg.d)
+    ds = min(cfg.d, max(B, (budget_elems // B) * B))
+    host = slab[:, :ds].cpu().numpy()
+    wh = w[:ds].cpu().numpy()
+    t0 = time.perf_counter()
+    planes = [oracle.quantize_pack(host[k], cfg.s, cfg.bucket, cfg.seed, 0, k) for k in range(cfg.K)]
+    t1 = time.perf_counter()
+    norms = np.stack([p[0] for p in planes])
+    sw = np.stack([p[1] for p in planes])
+    lw = np.stack([p[2] for p in planes])
+    t2 = time.perf_counter()
+    zbar = oracle.unpack_aggregate(norms, sw, lw, ds, cfg.s, cfg.bucket)
+    oracle.apply_update(wh, zbar, np.zeros(ds, np.float32))
+    t3 = time.perf_counter()
+    nb, nsw, nlw, _, _ = oracle.shape(ds, cfg.s, cfg.bucket)
+    P = 4 * (nb + nsw + nlw)
+    qb, ub = cfg.K * (4 * ds + P), cfg.K * P + 20 * ds
+    tq, tu = t1 - t0, t3 - t2
+    return {
+        "value": round((qb + ub) / (tq + tu) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"first {ds} of {cfg.d} coordinates of all {cfg.K} workers, one round "
+                  f"({cfg.K * ds} coordinate quantisations)",
+        "quantize_GBps": round(qb / tq / 1e9, 4), "aggregate_update_GBps": round(ub / tu / 1e9, 4),
+        "quantize_params_per_s": round(cfg.K * ds / tq), "aggregate_update_params_per_s": round(ds / tu),
+        "seconds": round(tq + tu, 2),
+    }
+
+
+def load_traffic(workload):
+    """Measured HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated on a
+    copy), if a summary for this workload has been committed under profiles/."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
+    if os.path.exists(path):
+        with open(path) as fh:
+            return json.load(fh)
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default: the largest, VGG-16-sized)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device copy (reference point for --pmc byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (K workers are K device buffers); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1901_03040_amd import binding as B
+    from paper_1901_03040_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    cfg = synth.by_name(args.config)
+    lay = B.qesgd_layout_query(cfg.d, cfg.s, cfg.bucket)
+    slab = synth.worker_slab(cfg, dev)
+    w = synth.snapshot(cfg, dev)
+    packed = B.alloc_packed(lay, cfg.K, dev)
+    zbar = torch.empty(cfg.d, device=dev)
+    u = torch.empty(cfg.d, device=dev)
+    zsum = torch.zeros(cfg.d, device=dev)
+    wsb = B.qesgd_workspace_bytes(cfg.d, cfg.s, cfg.bucket, cfg.K)
+    ws = torch.empty(max(wsb // 4, 1), dtype=torch.float32, device=dev) if wsb else None
+    stream = torch.cuda.current_stream()
+
+    if args.copy_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
+    def step(r, events=None):
+        if events is not None:
+            events[0].record(stream)
+        B.qesgd_quantize_pack_batched(slab, slab.stride(0), None, cfg.d, cfg.s, cfg.bucket, B.NORM_L2,
+                                      cfg.seed, r, cfg.K, packed, packed.stride(0), ws, stream)
+        if events is not None:
+            events[1].record(stream)
+        B.qesgd_unpack_aggregate_update(packed, packed.stride(0), cfg.K, cfg.d, cfg.s, cfg.bucket, w, zbar, u,
+                                        zsum, stream)
+        if events is not None:
+            events[2].record(stream)
+
+    for r in range(args.warmup):
+        step(r)
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for r in range(args.steps):
+        step(args.warmup + r, evs[r])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    tq = sorted(e[0].elapsed_time(e[1]) for e in evs)
+    tu = sorted(e[1].elapsed_time(e[2]) for e in evs)
+    tq_avg, tu_avg = sum(tq) / len(tq), sum(tu) / len(tu)
+    qb, ub = algorithmic_bytes(cfg, lay)
+    traffic = load_traffic(cfg.name) or {}
+
+    def phase(bytes_, ms_avg, ms_sorted, params):
+        return {"algorithmic_bytes": bytes_, "ms_avg": round(ms_avg, 4), "ms_median": round(ms_sorted[len(ms_sorted) // 2], 4),
+                "ms_min": round(ms_sorted[0], 4), "GBps": round(bytes_ / ms_avg / 1e6, 1),
+                "frac_of_hbm_peak": round(bytes_ / ms_avg / 1e6 / HBM_PEAK_GBPS, 4),
+                "params_per_s": round(params / ms_avg * 1e3)}
+
+    phases = {"quantize_pack": phase(qb, tq_avg, tq, cfg.K * cfg.d),
+              "unpack_aggregate_update": phase(ub, tu_avg, tu, cfg.d)}
+    dom = "quantize_pack" if tq_avg >= tu_avg else "unpack_aggregate_update"
+
+    def roofline(name):
+        ph = phases[name]
+        return {"kernel": name, "bound": "hbm", "achieved": ph["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": ph["frac_of_hbm_peak"], "traffic": traffic.get(name)}
+
+    out = {
+        "metric": "quantize+pack and unpack+aggregate+update GB/s (fp32 params) and % of HBM peak",
+        "value": round((qb + ub) / ms_step / 1e6, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: d={cfg.d} ({cfg.model}), K={cfg.K}, s={cfg.s}, bucket={cfg.bucket}, "
+                               f"entries {cfg.entries}, seed {cfg.seed}",
+                   "d": cfg.d, "K": cfg.K, "s": cfg.s, "bucket": cfg.bucket,
+                   "packed_bytes_per_worker": lay.payload_bytes},
+        "frac_of_hbm_peak": round((qb + ub) / ms_step / 1e6 / HBM_PEAK_GBPS, 4),
+        "params_per_s": round(cfg.K * cfg.d / ms_step * 1e3),
+        "phases": phases,
+        "roofline": roofline(dom),
+        "roofline_other": roofline("unpack_aggregate_update" if dom == "quantize_pack" else "quantize_pack"),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, slab, w, lay)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
