@@ -23,6 +23,7 @@ struct AParams {
     uint64_t level_words;
     uint32_t K;
     int32_t log2B;          // >= 0 when B is a power of two, else -1
+    uint32_t wave_uniform_bucket;   // 1 when every 512-aligned chunk lies inside one bucket
     float smax;
     float rcpK;             // exact 1/K when K is a power of two, else 0
 };
@@ -89,9 +90,26 @@ __device__ __forceinline__ uint32_t level_of(const uint32_t (&w)[4], int e) {
     return (w[bit >> 5] >> (bit & 31)) & mask;
 }
 
+// Sign flip without a branch: q ^ (shifted_sign & 0x80000000) in one v_bitop3
+// (truth table of a ^ (b & c) with a = 0xF0, b = 0xCC, c = 0xAA: 0x78).
+__device__ __forceinline__ float apply_sign(float q, uint32_t sign_in_bit31) {
+    return __uint_as_float(__builtin_amdgcn_bitop3_b32(__float_as_uint(q), sign_in_bit31, 0x80000000u, 0x78));
+}
+
+// One worker's contribution to the 8 coordinates of a lane: acc[e] += +-level_e * step.
 template <int M>
-__global__ void __launch_bounds__(256) k_unpack_aggregate_update(const AParams p) {
-    const uint64_t i = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) * kLaneElems;
+__device__ __forceinline__ void accumulate8(float (&acc)[8], uint32_t sbyte, const uint32_t (&w)[4], float step) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float q = (float)level_of<M>(w, e) * step;
+        acc[e] = acc[e] + apply_sign(q, sbyte << (31 - e));
+    }
+}
+
+// Ragged end of the vector (and shapes the wave-uniform path below does not cover): every
+// access guarded per lane, 8 consecutive coordinates per lane for all streams.
+template <int M>
+__device__ __forceinline__ void aggregate_lane_guarded(const AParams& p, uint64_t i) {
     if (i >= p.d) return;
     const uint64_t rem = p.d - i;
     const uint32_t nvalid = rem < 8 ? (uint32_t)rem : 8u;
@@ -100,7 +118,6 @@ __global__ void __launch_bounds__(256) k_unpack_aggregate_update(const AParams p
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
-
 #pragma unroll 4
     for (uint32_t k = 0; k < p.K; ++k) {
         const unsigned char* __restrict__ blk = p.packed + (uint64_t)k * p.packed_stride;
@@ -108,15 +125,8 @@ __global__ void __launch_bounds__(256) k_unpack_aggregate_update(const AParams p
         const uint32_t sbyte = (blk + p.signs_off)[i >> 3];
         uint32_t w[4];
         load_level_bits<M>(reinterpret_cast<const uint32_t*>(blk + p.levels_off), i, nvalid, p.level_words, w);
-        const float step = norm / p.smax;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float q = (float)level_of<M>(w, e) * step;
-            const uint32_t flip = ((sbyte >> e) & 1u) << 31;
-            acc[e] = acc[e] + __uint_as_float(__float_as_uint(q) ^ flip);
-        }
+        accumulate8<M>(acc, sbyte, w, norm / p.smax);
     }
-
     float z[8];
     if (p.rcpK != 0.0f) {
 #pragma unroll
@@ -143,25 +153,139 @@ __global__ void __launch_bounds__(256) k_unpack_aggregate_update(const AParams p
     }
 }
 
+// A wave owns 512 consecutive coordinates.  The codes are read with a lane owning 8
+// consecutive coordinates (one sign byte, 8*M level bits per worker); the fp32 vectors are
+// read and written with a lane owning one float4 of each 256-coordinate half, so that every
+// 128-bit access of a wave covers a contiguous KiB (a 32-byte lane stride would split every
+// store into half-filled requests).  z crosses from one layout to the other through 2 KiB of
+// LDS private to the wave.  UPDATE: w, u present.  When the bucket size is a multiple of 512
+// the whole wave shares a bucket: lane k divides worker k's scale once and the loop reads it
+// back as a scalar.
+template <int M, bool UPDATE, bool ZSUM, bool ZBAR>
+__global__ void __launch_bounds__(256) k_unpack_aggregate_update(const AParams p) {
+    __shared__ float4 stage[4][128];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint64_t wave_base = ((uint64_t)blockIdx.x * 4 + wave) * kChunk;
+    if (wave_base >= p.d) return;
+    if (wave_base + kChunk > p.d) {                       // ragged last wave
+        aggregate_lane_guarded<M>(p, wave_base + lane * kLaneElems);
+        return;
+    }
+    const uint64_t i = wave_base + lane * kLaneElems;     // code layout: 8 consecutive coordinates
+    const uint64_t ia = wave_base + lane * 4u;            // vector layout: float4 #lane of each half
+    const uint64_t ib = ia + 256u;
+
+    float4 wa, wb, sa, sb;
+    if (UPDATE) {
+        wa = *reinterpret_cast<const float4*>(p.w + ia);
+        wb = *reinterpret_cast<const float4*>(p.w + ib);
+    }
+    if (ZSUM) {
+        sa = *reinterpret_cast<const float4*>(p.zsum + ia);
+        sb = *reinterpret_cast<const float4*>(p.zsum + ib);
+    }
+
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+
+    if (p.wave_uniform_bucket) {
+        const uint64_t b = p.log2B >= 0 ? (wave_base >> p.log2B) : (wave_base / p.B);
+        float my_step = 0.0f;
+        if (lane < p.K) {
+            const float norm = reinterpret_cast<const float*>(p.packed + (uint64_t)lane * p.packed_stride + p.norms_off)[b];
+            my_step = norm / p.smax;
+        }
+        uint32_t k = 0;
+        for (; k + 4 <= p.K; k += 4) {                    // four workers' codes in flight at a time
+            uint32_t sbyte[4], w[4][4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const unsigned char* __restrict__ blk = p.packed + (uint64_t)(k + j) * p.packed_stride;
+                sbyte[j] = (blk + p.signs_off)[i >> 3];
+                load_level_bits<M>(reinterpret_cast<const uint32_t*>(blk + p.levels_off), i, 8u, p.level_words, w[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float step = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_step), k + j));
+                accumulate8<M>(acc, sbyte[j], w[j], step);
+            }
+        }
+        for (; k < p.K; ++k) {
+            const unsigned char* __restrict__ blk = p.packed + (uint64_t)k * p.packed_stride;
+            const uint32_t sbyte = (blk + p.signs_off)[i >> 3];
+            uint32_t w[4];
+            load_level_bits<M>(reinterpret_cast<const uint32_t*>(blk + p.levels_off), i, 8u, p.level_words, w);
+            const float step = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_step), k));
+            accumulate8<M>(acc, sbyte, w, step);
+        }
+    } else {
+        const uint64_t b = p.log2B >= 0 ? (i >> p.log2B) : (i / p.B);
+#pragma unroll 4
+        for (uint32_t k = 0; k < p.K; ++k) {
+            const unsigned char* __restrict__ blk = p.packed + (uint64_t)k * p.packed_stride;
+            const float norm = reinterpret_cast<const float*>(blk + p.norms_off)[b];
+            const uint32_t sbyte = (blk + p.signs_off)[i >> 3];
+            uint32_t w[4];
+            load_level_bits<M>(reinterpret_cast<const uint32_t*>(blk + p.levels_off), i, 8u, p.level_words, w);
+            accumulate8<M>(acc, sbyte, w, norm / p.smax);
+        }
+    }
+
+    float z[8];
+    if (p.rcpK != 0.0f) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) z[e] = acc[e] * p.rcpK;      // exact scaling by 2^-j == the division
+    } else {
+        const float fk = (float)p.K;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) z[e] = acc[e] / fk;
+    }
+
+    // lane-of-8 layout -> float4-per-half layout (same wave on both sides: LDS keeps program order)
+    stage[wave][2 * lane] = make_float4(z[0], z[1], z[2], z[3]);
+    stage[wave][2 * lane + 1] = make_float4(z[4], z[5], z[6], z[7]);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const float4 za = stage[wave][lane];
+    const float4 zb = stage[wave][64 + lane];
+
+    if (ZBAR) {
+        *reinterpret_cast<float4*>(p.zbar + ia) = za;
+        *reinterpret_cast<float4*>(p.zbar + ib) = zb;
+    }
+    if (UPDATE) {
+        *reinterpret_cast<float4*>(p.u + ia) = make_float4(wa.x + za.x, wa.y + za.y, wa.z + za.z, wa.w + za.w);
+        *reinterpret_cast<float4*>(p.u + ib) = make_float4(wb.x + zb.x, wb.y + zb.y, wb.z + zb.z, wb.w + zb.w);
+    }
+    if (ZSUM) {
+        *reinterpret_cast<float4*>(p.zsum + ia) = make_float4(sa.x + za.x, sa.y + za.y, sa.z + za.z, sa.w + za.w);
+        *reinterpret_cast<float4*>(p.zsum + ib) = make_float4(sb.x + zb.x, sb.y + zb.y, sb.z + zb.z, sb.w + zb.w);
+    }
+}
+
+// u = w + z, zsum += z: one float4 per lane so that every access of a wave is a contiguous KiB.
 __global__ void __launch_bounds__(256) k_apply_update(const float* w, const float* zbar,
                                                       float* u, float* zsum, uint64_t d) {
-    const uint64_t i = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) * kLaneElems;
+    const uint64_t i = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4u;
     if (i >= d) return;
-    const uint64_t rem = d - i;
-    const uint32_t nvalid = rem < 8 ? (uint32_t)rem : 8u;
-    float z[8], w8[8], u8[8];
-    load8(zbar, i, nvalid, z);
-    load8(w, i, nvalid, w8);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) u8[e] = w8[e] + z[e];
-    if (zsum) {
-        float s8[8];
-        load8(zsum, i, nvalid, s8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s8[e] = s8[e] + z[e];
-        store8(zsum, i, nvalid, s8);
+    if (i + 4 <= d) {
+        const float4 z = *reinterpret_cast<const float4*>(zbar + i);
+        const float4 a = *reinterpret_cast<const float4*>(w + i);
+        if (zsum) {
+            const float4 s = *reinterpret_cast<const float4*>(zsum + i);
+            *reinterpret_cast<float4*>(zsum + i) = make_float4(s.x + z.x, s.y + z.y, s.z + z.z, s.w + z.w);
+        }
+        *reinterpret_cast<float4*>(u + i) = make_float4(a.x + z.x, a.y + z.y, a.z + z.z, a.w + z.w);
+    } else {
+        for (uint64_t j = i; j < d; ++j) {
+            const float z = zbar[j];
+            const float a = w[j];
+            if (zsum) zsum[j] = zsum[j] + z;
+            u[j] = a + z;
+        }
     }
-    store8(u, i, nvalid, u8);
 }
 
 int check_launch() {
@@ -199,23 +323,35 @@ int launch_aggregate(const Shape& sh, const AggregateArgs& a) {
     p.smax = (float)(sh.s - 1);
     p.rcpK = ((a.K & (a.K - 1)) == 0) ? 1.0f / (float)a.K : 0.0f;
 
+    p.wave_uniform_bucket = (sh.B % kChunk == 0 || sh.nb == 1) ? 1u : 0u;
+
     const uint64_t lanes = (sh.d + kLaneElems - 1) / kLaneElems;
     const uint64_t blocks = (lanes + 255) / 256;
     if (blocks >= (1ull << 31)) return QESGD_ERR_DIM;
     const dim3 grid((uint32_t)blocks), block(256);
+    const bool upd = a.w_snap != nullptr, zs = a.zsum != nullptr, zb = a.zbar_out != nullptr;
+#define QESGD_LAUNCH_AGG(MM)                                                                              \
+    do {                                                                                                 \
+        if (upd && zs && zb) hipLaunchKernelGGL((k_unpack_aggregate_update<MM, true, true, true>), grid, block, 0, a.stream, p);        \
+        else if (upd && zs) hipLaunchKernelGGL((k_unpack_aggregate_update<MM, true, true, false>), grid, block, 0, a.stream, p);        \
+        else if (upd && zb) hipLaunchKernelGGL((k_unpack_aggregate_update<MM, true, false, true>), grid, block, 0, a.stream, p);        \
+        else if (upd) hipLaunchKernelGGL((k_unpack_aggregate_update<MM, true, false, false>), grid, block, 0, a.stream, p);             \
+        else hipLaunchKernelGGL((k_unpack_aggregate_update<MM, false, false, true>), grid, block, 0, a.stream, p);                      \
+    } while (0)
     switch (sh.m) {
-        case 1: hipLaunchKernelGGL(k_unpack_aggregate_update<1>, grid, block, 0, a.stream, p); break;
-        case 2: hipLaunchKernelGGL(k_unpack_aggregate_update<2>, grid, block, 0, a.stream, p); break;
-        case 4: hipLaunchKernelGGL(k_unpack_aggregate_update<4>, grid, block, 0, a.stream, p); break;
-        case 8: hipLaunchKernelGGL(k_unpack_aggregate_update<8>, grid, block, 0, a.stream, p); break;
-        default: hipLaunchKernelGGL(k_unpack_aggregate_update<16>, grid, block, 0, a.stream, p); break;
+        case 1: QESGD_LAUNCH_AGG(1); break;
+        case 2: QESGD_LAUNCH_AGG(2); break;
+        case 4: QESGD_LAUNCH_AGG(4); break;
+        case 8: QESGD_LAUNCH_AGG(8); break;
+        default: QESGD_LAUNCH_AGG(16); break;
     }
+#undef QESGD_LAUNCH_AGG
     return check_launch();
 }
 
 int launch_apply_update(const float* w, const float* zbar, float* u, float* zsum, uint64_t d,
                         hipStream_t stream) {
-    const uint64_t lanes = (d + kLaneElems - 1) / kLaneElems;
+    const uint64_t lanes = (d + 3) / 4;
     const uint64_t blocks = (lanes + 255) / 256;
     if (blocks >= (1ull << 31)) return QESGD_ERR_DIM;
     hipLaunchKernelGGL(k_apply_update, dim3((uint32_t)blocks), dim3(256), 0, stream, w, zbar, u, zsum, d);

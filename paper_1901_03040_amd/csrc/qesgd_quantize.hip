@@ -5,12 +5,20 @@
 // slots [b*N, (b+1)*N), N = bucket size zero-padded to a power of two, so that
 // every bucket starts on a power-of-two boundary whatever its length.  A lane
 // owns 8 consecutive slots (two 128-bit loads, one Philox call, one sign byte),
-// a wavefront owns CH chunks of 64 x 8 = 512 slots, a workgroup owns
+// a wavefront owns CH chunks of 64 x 8 = 512 slots, a workgroup owns a tile of
 // nwaves x CH x 512 slots.  The fp32 sum of squares is the balanced binary tree
 // over slot index bits: bits 0-2 inside the lane, bits 3-8 as an xor butterfly
-// over lanes (DPP for masks 1,2,4,8; cross-row exchange for 16,32), then the
+// over lanes (DPP for masks 1,2,4,8; row / half swaps for 16,32), then the
 // chunks of a wave, then the waves of a workgroup through LDS.  Every lane ends
 // with its bucket's total, so the scale never goes through memory.
+//
+// Two kernels share the arithmetic:
+//   k_quantize_pack_fast  power-of-two buckets, L2 scale, tiles that lie wholly
+//                         inside the vector.  N is a template parameter, so the
+//                         whole tile is straight-line code without guards.
+//   k_quantize_pack       everything else: ragged last tile, buckets that are
+//                         not a power of two, max-norm, tiny vectors, and the
+//                         second pass of buckets too wide for one workgroup.
 #include "qesgd_internal.h"
 
 namespace qesgd {
@@ -28,7 +36,9 @@ struct QParams {
     uint64_t nb;
     uint64_t norms_off, signs_off, levels_off;
     uint32_t log2N;
-    uint32_t tiles_per_worker;
+    uint32_t tile0;              // generic kernel: first tile it covers
+    uint32_t tiles_per_worker;   // generic kernel: tiles it covers per worker
+    uint32_t full_tiles;         // fast kernel: tiles per worker
     uint32_t key0, key1;
     uint32_t round;
     uint32_t worker0;
@@ -37,16 +47,20 @@ struct QParams {
 
 // ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11).  The key is wave-uniform, so its Weyl
-// sequence lives in scalar registers.
+// sequence lives in scalar registers; the three-way xor is one v_bitop3.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t (&o)[4]) {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
         const uint64_t pa = (uint64_t)0xD2511F53u * c0;
         const uint64_t pb = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+        const uint32_t n0 = xor3((uint32_t)(pb >> 32), c1, k0);
+        const uint32_t n2 = xor3((uint32_t)(pa >> 32), c3, k1);
         c1 = (uint32_t)pb;
         c3 = (uint32_t)pa;
         c0 = n0;
@@ -79,6 +93,21 @@ __device__ __forceinline__ float combine(float a, float b) {
     return fmaxf(a, b);
 }
 
+// The two halves of an exchange between 16-lane rows (lanes l and l ^ 16) or
+// between wave halves (l and l ^ 32): v_permlane16_swap / v_permlane32_swap hand
+// every lane its own row's value and the partner row's value, in some order;
+// the combine is commutative, so the order does not matter.
+template <int KIND>
+__device__ __forceinline__ float combine_xor16(float t) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+    return combine<KIND>(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+template <int KIND>
+__device__ __forceinline__ float combine_xor32(float t) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+    return combine<KIND>(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // Butterfly over the lanes that share a bucket (lanes_per_bucket = 1..64, a power
 // of two, wave-uniform).  The mirror steps fetch "the other half" because after
 // the previous steps all lanes of a half hold the same value; a + b == b + a, so
@@ -89,8 +118,8 @@ __device__ __forceinline__ float lane_butterfly(float t, uint32_t lanes_per_buck
     if (lanes_per_bucket > 2) t = combine<KIND>(t, dpp_f32<kDppXor2>(t));
     if (lanes_per_bucket > 4) t = combine<KIND>(t, dpp_f32<kDppHalfMirror>(t));
     if (lanes_per_bucket > 8) t = combine<KIND>(t, dpp_f32<kDppRowMirror>(t));
-    if (lanes_per_bucket > 16) t = combine<KIND>(t, __shfl_xor(t, 16, 64));
-    if (lanes_per_bucket > 32) t = combine<KIND>(t, __shfl_xor(t, 32, 64));
+    if (lanes_per_bucket > 16) t = combine_xor16<KIND>(t);
+    if (lanes_per_bucket > 32) t = combine_xor32<KIND>(t);
     return t;
 }
 
@@ -105,6 +134,248 @@ __device__ __forceinline__ float lane_tree(const float (&v)[8]) {
                  fmaxf(fmaxf(fabsf(v[4]), fabsf(v[5])), fmaxf(fabsf(v[6]), fabsf(v[7]))));
 }
 
+// Pairwise tree over up to 16 wave totals parked in LDS; entries beyond `count`
+// are +0 (adding +0 is exact, so the padded tree equals the tree over `count`).
+// `sm` must have 32 readable floats: a hoisted read of sm[base + r] stays inside.
+template <int KIND>
+__device__ __forceinline__ float lds_tree16(const float* sm, uint32_t base, uint32_t count) {
+    float a[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) a[r] = ((uint32_t)r < count) ? sm[base + r] : 0.0f;
+#pragma unroll
+    for (int w = 1; w < 16; w <<= 1) {
+#pragma unroll
+        for (int r = 0; r < 16; r += 2 * w) a[r] = combine<KIND>(a[r], a[r + w]);
+    }
+    return a[0];
+}
+
+// ---------------------------------------------------------------------------
+// Rounding and in-lane packing of the 8 coordinates of a lane.
+//   fixed = trunc(min(|v| * inv, smax) * 2^16) = floor(a) * 2^16 + trunc(frac(a) * 2^16)
+//   level = (fixed + r16) >> 16        (the carry out of the low half rounds up)
+// inv * 2^16 is folded into the scale when it is finite: scaling by a power of
+// two commutes with rounding, and a product that underflows truncates to 0
+// either way.  bits[] receives the 8*M level bits (M = 1: low byte, M = 2: low
+// half, M = 4: one word, M = 8: two words, M = 16: four words).
+// ---------------------------------------------------------------------------
+template <int M>
+__device__ __forceinline__ void round_and_pack(const float (&v)[8], const uint32_t (&rnd)[4], float inv,
+                                               float smax, uint32_t& sign_byte, uint32_t (&bits)[4]) {
+    uint32_t y[8];
+    const float inv16 = inv * 65536.0f;
+    if (inv16 < INFINITY) {
+        const float smax16 = smax * 65536.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t word = rnd[e >> 1];
+            const uint32_t r16 = (e & 1) ? (word >> 16) : (word & 0xFFFFu);
+            y[e] = (uint32_t)fminf(fabsf(v[e]) * inv16, smax16) + r16;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t word = rnd[e >> 1];
+            const uint32_t r16 = (e & 1) ? (word >> 16) : (word & 0xFFFFu);
+            y[e] = (uint32_t)(fminf(fabsf(v[e]) * inv, smax) * 65536.0f) + r16;
+        }
+    }
+    uint32_t sb = 0;
+#pragma unroll
+    for (int e = 7; e >= 0; --e) sb = sb + sb + (v[e] < 0.0f ? 1u : 0u);   // v_cmp + v_addc
+    sign_byte = sb;
+    bits[0] = bits[1] = bits[2] = bits[3] = 0;
+    if (M == 1 || M == 2 || M == 4) {
+        uint32_t w = y[0] >> 16;
+#pragma unroll
+        for (int e = 1; e < 8; ++e) w |= (y[e] >> 16) << (M * e);
+        bits[0] = w;
+    } else if (M == 8) {
+        bits[0] = (y[0] >> 16) | ((y[1] >> 16) << 8) | ((y[2] >> 16) << 16) | ((y[3] >> 16) << 24);
+        bits[1] = (y[4] >> 16) | ((y[5] >> 16) << 8) | ((y[6] >> 16) << 16) | ((y[7] >> 16) << 24);
+    } else {
+        bits[0] = (y[0] >> 16) | (y[1] & 0xFFFF0000u);
+        bits[1] = (y[2] >> 16) | (y[3] & 0xFFFF0000u);
+        bits[2] = (y[4] >> 16) | (y[5] & 0xFFFF0000u);
+        bits[3] = (y[6] >> 16) | (y[7] & 0xFFFF0000u);
+    }
+}
+
+__device__ __forceinline__ float inverse_step(float norm, float smax) {
+    float inv = smax / norm;
+    if (!(inv < INFINITY)) inv = 0.0f;     // norm 0 (or reciprocal overflow): every level is 0
+    return inv;
+}
+
+// Cross-lane assembly of words and the stores, for a lane whose 8 coordinates
+// start at coordinate i (a multiple of 8) of which nvalid (0..8) exist.
+// sign_words / level_words point at word 0 of the planes.
+template <int M>
+__device__ __forceinline__ void store_codes(uint32_t* __restrict__ sign_words, uint32_t* __restrict__ level_words,
+                                            uint64_t i, uint32_t nvalid, uint32_t lane,
+                                            uint32_t sign_byte, const uint32_t (&bits)[4]) {
+    {
+        uint32_t w = sign_byte << (8u * (lane & 3u));
+        w |= dpp_u32<kDppXor1>(w);
+        w |= dpp_u32<kDppXor2>(w);
+        if ((lane & 3u) == 0u && nvalid > 0) sign_words[i >> 5] = w;
+    }
+    if (M == 1) {
+        uint32_t w = bits[0] << (8u * (lane & 3u));
+        w |= dpp_u32<kDppXor1>(w);
+        w |= dpp_u32<kDppXor2>(w);
+        if ((lane & 3u) == 0u && nvalid > 0) level_words[i >> 5] = w;
+    } else if (M == 2) {
+        uint32_t w = bits[0] << (16u * (lane & 1u));
+        w |= dpp_u32<kDppXor1>(w);
+        if ((lane & 1u) == 0u && nvalid > 0) level_words[i >> 4] = w;
+    } else if (M == 4) {
+        if (nvalid > 0) level_words[i >> 3] = bits[0];
+    } else if (M == 8) {
+        if (nvalid == 8) {
+            *reinterpret_cast<uint2*>(level_words + (i >> 2)) = make_uint2(bits[0], bits[1]);
+        } else {
+            if (nvalid > 0) level_words[i >> 2] = bits[0];
+            if (nvalid > 4) level_words[(i >> 2) + 1] = bits[1];
+        }
+    } else {
+        if (nvalid == 8) {
+            *reinterpret_cast<uint4*>(level_words + (i >> 1)) = make_uint4(bits[0], bits[1], bits[2], bits[3]);
+        } else {
+            if (nvalid > 0) level_words[i >> 1] = bits[0];
+            if (nvalid > 2) level_words[(i >> 1) + 1] = bits[1];
+            if (nvalid > 4) level_words[(i >> 1) + 2] = bits[2];
+            if (nvalid > 6) level_words[(i >> 1) + 3] = bits[3];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Fast kernel.  Geometry per bucket size: tile = NW waves x CH chunks x 512.
+// ---------------------------------------------------------------------------
+template <int LOG2N>
+struct Geo {
+    static constexpr int CH = (LOG2N == 15) ? 4 : 2;
+    static constexpr int NW = (LOG2N <= 12) ? 4 : (LOG2N == 13 ? 8 : 16);
+    static constexpr uint32_t TILE = (uint32_t)NW * CH * kChunk;
+};
+
+template <int CH, bool CENTER>
+__device__ __forceinline__ void load_tile(const float* __restrict__ xt, const float* __restrict__ ct,
+                                          uint32_t lane_off, float (&v)[CH][8]) {
+    float4 a[CH], b[CH], ca[CH], cb[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const uint32_t o = lane_off + (uint32_t)c * kChunk;
+        a[c] = *reinterpret_cast<const float4*>(xt + o);
+        b[c] = *reinterpret_cast<const float4*>(xt + o + 4);
+        if (CENTER) {
+            ca[c] = *reinterpret_cast<const float4*>(ct + o);
+            cb[c] = *reinterpret_cast<const float4*>(ct + o + 4);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        v[c][0] = a[c].x; v[c][1] = a[c].y; v[c][2] = a[c].z; v[c][3] = a[c].w;
+        v[c][4] = b[c].x; v[c][5] = b[c].y; v[c][6] = b[c].z; v[c][7] = b[c].w;
+        if (CENTER) {
+            v[c][0] -= ca[c].x; v[c][1] -= ca[c].y; v[c][2] -= ca[c].z; v[c][3] -= ca[c].w;
+            v[c][4] -= cb[c].x; v[c][5] -= cb[c].y; v[c][6] -= cb[c].z; v[c][7] -= cb[c].w;
+        }
+    }
+}
+
+// Everything a workgroup needs to know about its worker, in registers.
+struct FastCtx {
+    float* __restrict__ norms;
+    uint32_t* __restrict__ signs;
+    uint32_t* __restrict__ levels;
+    uint32_t lane, wave, lane_off, worker, round, key0, key1;
+    float smax;
+};
+
+// One tile: bucket totals, scales, variates, rounding, packing, stores.
+template <int M, int LOG2N>
+__device__ __forceinline__ void process_tile(const FastCtx& cx, float (&v)[Geo<LOG2N>::CH][8], uint32_t t, float* sm) {
+    constexpr int CH = Geo<LOG2N>::CH;
+    constexpr uint32_t N = 1u << LOG2N;
+    constexpr uint32_t TILE = Geo<LOG2N>::TILE;
+    constexpr uint32_t LPB = (N < kChunk ? N : kChunk) / kLaneElems;                       // lanes per bucket
+    constexpr int CPB = N <= kChunk ? 1 : (int)(N / kChunk < (uint32_t)CH ? N / kChunk : (uint32_t)CH);  // chunks per bucket in a wave
+    constexpr uint32_t WPB = N <= CH * kChunk ? 1u : N / (CH * kChunk);                     // waves per bucket
+    constexpr int KIND = QESGD_NORM_L2;
+    const uint64_t e0 = (uint64_t)t * TILE;                      // first coordinate of the tile
+
+    float tot[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) tot[c] = lane_butterfly<KIND>(lane_tree<KIND>(v[c]), LPB);
+    if (CPB > 1) {
+#pragma unroll
+        for (int w = 1; w < CPB; w <<= 1) {
+#pragma unroll
+            for (int c = 0; c < CH; c += 2 * w) tot[c] = combine<KIND>(tot[c], tot[c + w]);
+        }
+    }
+    if (WPB > 1) {
+        if (cx.lane == 0) sm[cx.wave] = tot[0];
+        __syncthreads();
+        tot[0] = lds_tree16<KIND>(sm, cx.wave & ~(WPB - 1u), WPB);
+    }
+
+    float inv = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const uint32_t off = cx.lane_off + (uint32_t)c * kChunk;
+        if (c % CPB == 0) {                                       // first chunk of a bucket (or of its part in this wave)
+            const float norm = sqrtf(tot[c]);
+            inv = inverse_step(norm, cx.smax);
+            if ((off & (N - 1u)) == 0u) cx.norms[(e0 >> LOG2N) + (off >> LOG2N)] = norm;
+        }
+        const uint64_t i = e0 + off;
+        const uint64_t g = i >> 3;
+        uint32_t rnd[4];
+        philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), cx.worker, cx.round, cx.key0, cx.key1, rnd);
+        uint32_t sign_byte, bits[4];
+        round_and_pack<M>(v[c], rnd, inv, cx.smax, sign_byte, bits);
+        store_codes<M>(cx.signs, cx.levels, i, 8u, cx.lane, sign_byte, bits);
+    }
+}
+
+// One tile per workgroup.  (Walking several tiles per workgroup with the next tile's loads
+// in flight was measured and is slower: the packed stores of a long-lived workgroup spread
+// out in time and the mixed read/write stream to HBM loses more than the prefetch gains.)
+template <int M, int LOG2N, bool CENTER>
+__global__ void __launch_bounds__(Geo<LOG2N>::NW * 64) k_quantize_pack_fast(const QParams p) {
+    constexpr int CH = Geo<LOG2N>::CH;
+    constexpr uint32_t TILE = Geo<LOG2N>::TILE;
+    __shared__ float sm[32];
+
+    const uint32_t k = blockIdx.x / p.full_tiles;
+    const uint32_t t = blockIdx.x - k * p.full_tiles;
+    const float* __restrict__ xk = p.x + (uint64_t)k * p.x_stride;
+    const float* __restrict__ ck = p.center;
+    unsigned char* __restrict__ out = p.packed + (uint64_t)k * p.packed_stride;
+    FastCtx cx;
+    cx.norms = reinterpret_cast<float*>(out + p.norms_off);
+    cx.signs = reinterpret_cast<uint32_t*>(out + p.signs_off);
+    cx.levels = reinterpret_cast<uint32_t*>(out + p.levels_off);
+    cx.lane = threadIdx.x & 63u;
+    cx.wave = threadIdx.x >> 6;
+    cx.lane_off = cx.wave * (uint32_t)(CH * kChunk) + cx.lane * kLaneElems;   // coordinate offset inside a tile
+    cx.worker = p.worker0 + k;
+    cx.round = p.round;
+    cx.key0 = p.key0;
+    cx.key1 = p.key1;
+    cx.smax = p.smax;
+
+    float buf[CH][8];
+    load_tile<CH, CENTER>(xk + (uint64_t)t * TILE, ck + (uint64_t)t * TILE, cx.lane_off, buf);
+    process_tile<M, LOG2N>(cx, buf, t, sm);
+}
+
+// ---------------------------------------------------------------------------
+// Generic kernel.
+// ---------------------------------------------------------------------------
 // Where the 8 slots of this lane fall: bucket, first coordinate, how many of
 // them are real coordinates (0..8), and whether they open the bucket.
 struct LaneSpan {
@@ -156,33 +427,16 @@ __device__ __forceinline__ void load_lane(const float* __restrict__ x, const flo
     }
 }
 
-// Pairwise tree over up to 16 wave totals parked in LDS; entries beyond `count`
-// are +0 (adding +0 is exact, so the padded tree equals the tree over `count`).
-template <int KIND>
-__device__ __forceinline__ float lds_tree16(const float* sm, uint32_t base, uint32_t count) {
-    float a[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) a[r] = ((uint32_t)r < count) ? sm[base + r] : 0.0f;
-#pragma unroll
-    for (int w = 1; w < 16; w <<= 1) {
-#pragma unroll
-        for (int r = 0; r < 16; r += 2 * w) a[r] = combine<KIND>(a[r], a[r + w]);
-    }
-    return a[0];
-}
-
-// ---------------------------------------------------------------------------
-// The fused kernel.  PRE = true: the scales were computed by the partial-sum
-// passes below and are read from the norms plane.
-// ---------------------------------------------------------------------------
+// PRE = true: the scales were computed by the partial-sum passes below and are
+// read from the norms plane.
 template <int M, int CH, int KIND, bool PRE>
 __global__ void k_quantize_pack(const QParams p) {
-    __shared__ float sm[32];   // 16 wave totals; the upper half stays unused so a hoisted read of sm[base + r] stays inside
+    __shared__ float sm[32];
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
     const uint32_t nwaves = blockDim.x >> 6;
     const uint32_t k = blockIdx.x / p.tiles_per_worker;
-    const uint32_t tile = blockIdx.x - k * p.tiles_per_worker;
+    const uint32_t tile = p.tile0 + (blockIdx.x - k * p.tiles_per_worker);
     const float* __restrict__ x = p.x + (uint64_t)k * p.x_stride;
     unsigned char* __restrict__ out = p.packed + (uint64_t)k * p.packed_stride;
     float* __restrict__ norms = reinterpret_cast<float*>(out + p.norms_off);
@@ -193,16 +447,10 @@ __global__ void k_quantize_pack(const QParams p) {
 
     LaneSpan span[CH];
     float v[CH][8];
-    uint32_t rnd[CH][4];
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
         span[c] = lane_span(slot0 + (uint64_t)c * kChunk, p);
         load_lane(x, p.center, span[c], v[c]);
-    }
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        const uint64_t g = span[c].i >> 3;
-        philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), p.worker0 + k, p.round, p.key0, p.key1, rnd[c]);
     }
 
     float norm[CH];
@@ -244,72 +492,14 @@ __global__ void k_quantize_pack(const QParams p) {
         }
     }
 
-    const float smax = p.smax;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-        float inv = smax / norm[c];
-        if (!(inv < INFINITY)) inv = 0.0f;
-        uint32_t lvl[8];
-        uint32_t sbyte = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float a = fminf(fabsf(v[c][e]) * inv, smax);
-            const uint32_t fixed = (uint32_t)(a * 65536.0f);           // floor(a)*2^16 + trunc(frac(a)*2^16)
-            const uint32_t word = rnd[c][e >> 1];
-            const uint32_t r16 = (e & 1) ? (word >> 16) : (word & 0xFFFFu);
-            lvl[e] = (fixed + r16) >> 16;                              // carry out of the low half = round up
-            sbyte |= (v[c][e] < 0.0f ? 1u : 0u) << e;
-        }
-        const uint32_t nvalid = span[c].nvalid;
-        const uint64_t i = span[c].i;
-        // sign plane: 4 lanes make a word
-        {
-            uint32_t w = sbyte << (8u * (lane & 3u));
-            w |= dpp_u32<kDppXor1>(w);
-            w |= dpp_u32<kDppXor2>(w);
-            if ((lane & 3u) == 0u && nvalid > 0) signs[i >> 5] = w;
-        }
-        if (M == 1) {
-            uint32_t lb = 0;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) lb |= lvl[e] << e;
-            uint32_t w = lb << (8u * (lane & 3u));
-            w |= dpp_u32<kDppXor1>(w);
-            w |= dpp_u32<kDppXor2>(w);
-            if ((lane & 3u) == 0u && nvalid > 0) levels[i >> 5] = w;
-        } else if (M == 2) {
-            uint32_t lb = 0;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) lb |= lvl[e] << (2 * e);
-            uint32_t w = lb << (16u * (lane & 1u));
-            w |= dpp_u32<kDppXor1>(w);
-            if ((lane & 1u) == 0u && nvalid > 0) levels[i >> 4] = w;
-        } else if (M == 4) {
-            uint32_t w = 0;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) w |= lvl[e] << (4 * e);
-            if (nvalid > 0) levels[i >> 3] = w;
-        } else if (M == 8) {
-            const uint32_t w0 = lvl[0] | (lvl[1] << 8) | (lvl[2] << 16) | (lvl[3] << 24);
-            const uint32_t w1 = lvl[4] | (lvl[5] << 8) | (lvl[6] << 16) | (lvl[7] << 24);
-            if (nvalid == 8) {
-                *reinterpret_cast<uint2*>(levels + (i >> 2)) = make_uint2(w0, w1);
-            } else {
-                if (nvalid > 0) levels[i >> 2] = w0;
-                if (nvalid > 4) levels[(i >> 2) + 1] = w1;
-            }
-        } else {  // M == 16
-            const uint32_t w0 = lvl[0] | (lvl[1] << 16), w1 = lvl[2] | (lvl[3] << 16);
-            const uint32_t w2 = lvl[4] | (lvl[5] << 16), w3 = lvl[6] | (lvl[7] << 16);
-            if (nvalid == 8) {
-                *reinterpret_cast<uint4*>(levels + (i >> 1)) = make_uint4(w0, w1, w2, w3);
-            } else {
-                if (nvalid > 0) levels[i >> 1] = w0;
-                if (nvalid > 2) levels[(i >> 1) + 1] = w1;
-                if (nvalid > 4) levels[(i >> 1) + 2] = w2;
-                if (nvalid > 6) levels[(i >> 1) + 3] = w3;
-            }
-        }
+        const uint64_t g = span[c].i >> 3;
+        uint32_t rnd[4];
+        philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), p.worker0 + k, p.round, p.key0, p.key1, rnd);
+        uint32_t sign_byte, bits[4];
+        round_and_pack<M>(v[c], rnd, inverse_step(norm[c], p.smax), p.smax, sign_byte, bits);
+        store_codes<M>(signs, levels, span[c].i, span[c].nvalid, lane, sign_byte, bits);
     }
 }
 
@@ -322,7 +512,7 @@ __global__ void k_quantize_pack(const QParams p) {
 template <int KIND>
 __global__ void k_tile_partials(const QParams p) {
     constexpr int CH = 2;
-    __shared__ float sm[32];   // 16 wave totals; the upper half stays unused so a hoisted read of sm[base + r] stays inside
+    __shared__ float sm[16];
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
     const uint32_t k = blockIdx.x / p.tiles_per_worker;
@@ -364,23 +554,60 @@ __global__ void k_finish_norms(const QParams p, uint64_t P) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// Launch plumbing.
+// ---------------------------------------------------------------------------
 template <int M, int CH, bool PRE>
-int launch_kind(const QParams& p, uint32_t norm_kind, dim3 grid, dim3 block, hipStream_t st) {
+void launch_kind(const QParams& p, uint32_t norm_kind, dim3 grid, dim3 block, hipStream_t st) {
     if (norm_kind == QESGD_NORM_L2)
         hipLaunchKernelGGL((k_quantize_pack<M, CH, QESGD_NORM_L2, PRE>), grid, block, 0, st, p);
     else
         hipLaunchKernelGGL((k_quantize_pack<M, CH, QESGD_NORM_MAX, PRE>), grid, block, 0, st, p);
-    return 0;
 }
 
 template <int CH, bool PRE>
-int launch_m(const QParams& p, uint32_t m, uint32_t norm_kind, dim3 grid, dim3 block, hipStream_t st) {
+void launch_m(const QParams& p, uint32_t m, uint32_t norm_kind, dim3 grid, dim3 block, hipStream_t st) {
     switch (m) {
-        case 1: return launch_kind<1, CH, PRE>(p, norm_kind, grid, block, st);
-        case 2: return launch_kind<2, CH, PRE>(p, norm_kind, grid, block, st);
-        case 4: return launch_kind<4, CH, PRE>(p, norm_kind, grid, block, st);
-        case 8: return launch_kind<8, CH, PRE>(p, norm_kind, grid, block, st);
-        default: return launch_kind<16, CH, PRE>(p, norm_kind, grid, block, st);
+        case 1: launch_kind<1, CH, PRE>(p, norm_kind, grid, block, st); break;
+        case 2: launch_kind<2, CH, PRE>(p, norm_kind, grid, block, st); break;
+        case 4: launch_kind<4, CH, PRE>(p, norm_kind, grid, block, st); break;
+        case 8: launch_kind<8, CH, PRE>(p, norm_kind, grid, block, st); break;
+        default: launch_kind<16, CH, PRE>(p, norm_kind, grid, block, st); break;
+    }
+}
+
+template <int M, int LOG2N>
+void launch_fast_one(const QParams& p, uint32_t blocks, hipStream_t st) {
+    if (p.center)
+        hipLaunchKernelGGL((k_quantize_pack_fast<M, LOG2N, true>), dim3(blocks), dim3(Geo<LOG2N>::NW * 64), 0, st, p);
+    else
+        hipLaunchKernelGGL((k_quantize_pack_fast<M, LOG2N, false>), dim3(blocks), dim3(Geo<LOG2N>::NW * 64), 0, st, p);
+}
+
+template <int M>
+void launch_fast_n(const QParams& p, uint32_t blocks, hipStream_t st) {
+    switch (p.log2N) {
+        case 5: launch_fast_one<M, 5>(p, blocks, st); break;
+        case 6: launch_fast_one<M, 6>(p, blocks, st); break;
+        case 7: launch_fast_one<M, 7>(p, blocks, st); break;
+        case 8: launch_fast_one<M, 8>(p, blocks, st); break;
+        case 9: launch_fast_one<M, 9>(p, blocks, st); break;
+        case 10: launch_fast_one<M, 10>(p, blocks, st); break;
+        case 11: launch_fast_one<M, 11>(p, blocks, st); break;
+        case 12: launch_fast_one<M, 12>(p, blocks, st); break;
+        case 13: launch_fast_one<M, 13>(p, blocks, st); break;
+        case 14: launch_fast_one<M, 14>(p, blocks, st); break;
+        default: launch_fast_one<M, 15>(p, blocks, st); break;
+    }
+}
+
+void launch_fast(const QParams& p, uint32_t m, uint32_t blocks, hipStream_t st) {
+    switch (m) {
+        case 1: launch_fast_n<1>(p, blocks, st); break;
+        case 2: launch_fast_n<2>(p, blocks, st); break;
+        case 4: launch_fast_n<4>(p, blocks, st); break;
+        case 8: launch_fast_n<8>(p, blocks, st); break;
+        default: launch_fast_n<16>(p, blocks, st); break;
     }
 }
 
@@ -418,7 +645,7 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
 
     const uint64_t slots = sh.nb * sh.N;                 // slot space of one worker
     const bool two_pass = sh.N > kMaxSinglePassBucket;
-    uint32_t ch = 2, nwaves = 4;
+    uint32_t ch = 2, nwaves = 4;                         // the same geometry as Geo<log2N>
     if (!two_pass) {
         if (sh.N == 8192) nwaves = 8;
         else if (sh.N == 16384) nwaves = 16;
@@ -427,11 +654,12 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
     const uint64_t tile = (uint64_t)nwaves * ch * kChunk;
     const uint64_t tiles = (slots + tile - 1) / tile;
     if (tiles * a.K >= (1ull << 31)) return QESGD_ERR_DIM;
-    p.tiles_per_worker = (uint32_t)tiles;
-    const dim3 grid((uint32_t)(tiles * a.K));
     const dim3 block(nwaves * kWaveSize);
 
     if (two_pass) {
+        p.tile0 = 0;
+        p.tiles_per_worker = (uint32_t)tiles;
+        const dim3 grid((uint32_t)(tiles * a.K));
         const uint64_t P = sh.N / kPartialTile;          // tiles == nb * P
         if (a.norm_kind == QESGD_NORM_L2) {
             hipLaunchKernelGGL(k_tile_partials<QESGD_NORM_L2>, grid, block, 0, a.stream, p);
@@ -443,10 +671,25 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
         const int rc = check_launch();
         if (rc != QESGD_OK) return rc;
         launch_m<2, true>(p, sh.m, a.norm_kind, grid, block, a.stream);
-    } else if (ch == 2) {
-        launch_m<2, false>(p, sh.m, a.norm_kind, grid, block, a.stream);
-    } else {
-        launch_m<4, false>(p, sh.m, a.norm_kind, grid, block, a.stream);
+        return check_launch();
+    }
+
+    // Tiles that lie wholly inside the vector go to the fast kernel when the bucket is a
+    // power of two (slot == coordinate) and the scale is the L2 norm.
+    uint64_t full_tiles = 0;
+    if (a.norm_kind == QESGD_NORM_L2 && sh.N == sh.B && sh.log2N >= 5) full_tiles = sh.d / tile;
+    if (full_tiles > 0) {
+        p.full_tiles = (uint32_t)full_tiles;
+        launch_fast(p, sh.m, (uint32_t)(full_tiles * a.K), a.stream);
+        const int rc = check_launch();
+        if (rc != QESGD_OK) return rc;
+    }
+    if (tiles > full_tiles) {
+        p.tile0 = (uint32_t)full_tiles;
+        p.tiles_per_worker = (uint32_t)(tiles - full_tiles);
+        const dim3 grid((uint32_t)((tiles - full_tiles) * a.K));
+        if (ch == 2) launch_m<2, false>(p, sh.m, a.norm_kind, grid, block, a.stream);
+        else launch_m<4, false>(p, sh.m, a.norm_kind, grid, block, a.stream);
     }
     return check_launch();
 }
