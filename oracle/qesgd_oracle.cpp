@@ -37,7 +37,9 @@
 // variate; unbiasedness and the variance bound of Lemma 1 by enumeration and by
 // Monte Carlo; the summation order on rounding-sensitive hand cases; pack /
 // unpack round trips and a hand-written word example; aggregate / update against
-// double precision and the epoch-mean identity.
+// double precision and the epoch-mean identity; the fixed-grid quantiser of
+// Eq. (1)-(2) by enumeration of the variate (probabilities, clamp cases, both
+// halves of Lemma 1) and a hand-written code word.
 // Parity unpinned: none of the functions below; the convergence behaviour of
 // the full method (Theorem 1) is outside this path.
 
@@ -324,6 +326,79 @@ void qo_apply_update(const float* w_snap, const float* zbar, float* u, float* zs
         u[i] = ui;
         if (zsum) { const float zs = zsum[i] + zbar[i]; zsum[i] = zs; }
     }
+}
+
+// End of an epoch (last step of Alg. 3): w_{t+1} = w_t + (1/K_t) * sum_k z_{t,k}; the
+// running sum restarts at 0 for the next epoch (z starts at 0 again, Alg. 2 first step).
+void qo_epoch_commit(float* w, float* zsum, uint32_t rounds, uint64_t d) {
+    const float kt = (float)rounds;
+    for (uint64_t i = 0; i < d; ++i) {
+        const float mean = zsum[i] / kt;
+        const float wi = w[i] + mean;
+        w[i] = wi;
+        zsum[i] = 0.0f;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The quantiser exactly as the paper writes it (Sec. 2.1, Eq. (1)-(2)): a fixed
+// grid {delta * k : -2^(b-1) <= k <= 2^(b-1) - 1} with a caller-chosen step
+// delta (the schedule delta_t of Sec. 4 / Sec. 5 is the caller's), values outside
+// the range are clamped to its ends, values inside are rounded down or up with
+// probability proportional to the distance to the other neighbour.
+// Readings: a = fl(v / delta) is formed in fp32; the variate has 16 bits and
+// rounds up iff r + trunc(frac(a) * 2^16) >= 2^16 (as above); the code of k is its
+// b-bit two's complement, b in {2, 4, 8, 16}, packed like the level plane
+// (coordinate i at bit (i*b) mod 32 of word (i*b)/32).
+// ---------------------------------------------------------------------------
+int32_t qo_fixed_round(float v, float delta, uint32_t b, uint32_t r16) {
+    const float lo = -(float)(1u << (b - 1));            // -2^(b-1)
+    const float hi = (float)((1u << (b - 1)) - 1u);      //  2^(b-1) - 1
+    float a = v / delta;
+    if (a >= hi) return (int32_t)hi;                     // Eq. (2), first case
+    if (a <= lo) return (int32_t)lo;                     // Eq. (2), last case
+    const float l = floorf(a);
+    const float f = a - l;                               // fp32: exact for a >= 0; a tiny negative a gives 1
+    const uint32_t T = (uint32_t)(f * 65536.0f);         // 0 .. 65536
+    const uint32_t up = (r16 + T) >> 16;                 // 0 or 1
+    return (int32_t)l + (int32_t)up;
+}
+
+int qo_fixed_code_bits_ok(uint32_t b) { return (b == 2 || b == 4 || b == 8 || b == 16) ? 1 : 0; }
+
+// codes: ceil(d*b/32) words.  v = x, or x - center when center is given.
+int qo_quantize_fixed(const float* x, const float* center, uint64_t d, float delta, uint32_t b,
+                      uint64_t seed, uint32_t round, uint32_t worker, uint32_t* codes) {
+    if (!qo_fixed_code_bits_ok(b) || d == 0 || !(delta > 0.0f) || !(delta < INFINITY)) return -1;
+    const uint64_t nw = (d * (uint64_t)b + 31) / 32;
+    const uint32_t mask = (b == 32) ? 0xFFFFFFFFu : ((1u << b) - 1u);
+    for (uint64_t w = 0; w < nw; ++w) codes[w] = 0;
+    for (uint64_t i = 0; i < d; ++i) {
+        float v = x[i];
+        if (center) { const float diff = x[i] - center[i]; v = diff; }
+        const int32_t k = qo_fixed_round(v, delta, b, uniform16(seed, round, worker, i));
+        const uint64_t bit = i * (uint64_t)b;
+        codes[bit >> 5] |= ((uint32_t)k & mask) << (bit & 31);
+    }
+    return 0;
+}
+
+// z = delta * k, u = w + z, zsum += z (zsum, z_out may be null).
+int qo_dequantize_fixed_update(const uint32_t* codes, uint64_t d, float delta, uint32_t b,
+                               const float* w_snap, float* z_out, float* u, float* zsum) {
+    if (!qo_fixed_code_bits_ok(b) || d == 0) return -1;
+    const uint32_t mask = (1u << b) - 1u;
+    for (uint64_t i = 0; i < d; ++i) {
+        const uint64_t bit = i * (uint64_t)b;
+        uint32_t c = (codes[bit >> 5] >> (bit & 31)) & mask;
+        int32_t k = (int32_t)c;
+        if (c & (1u << (b - 1))) k -= (int32_t)(1u << b);            // sign extension
+        const float z = (float)k * delta;
+        if (z_out) z_out[i] = z;
+        if (u) { const float ui = w_snap[i] + z; u[i] = ui; }
+        if (zsum) { const float zs = zsum[i] + z; zsum[i] = zs; }
+    }
+    return 0;
 }
 
 }  // extern "C"

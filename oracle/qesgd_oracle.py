@@ -66,6 +66,14 @@ def lib():
         L.qo_unpack_aggregate.restype = C.c_int
         L.qo_apply_update.argtypes = [vp, vp, vp, vp, u64]
         L.qo_apply_update.restype = None
+        L.qo_epoch_commit.argtypes = [vp, vp, u32, u64]
+        L.qo_epoch_commit.restype = None
+        L.qo_fixed_round.argtypes = [f32, f32, u32, u32]
+        L.qo_fixed_round.restype = C.c_int32
+        L.qo_quantize_fixed.argtypes = [vp, vp, u64, f32, u32, u64, u32, u32, vp]
+        L.qo_quantize_fixed.restype = C.c_int
+        L.qo_dequantize_fixed_update.argtypes = [vp, u64, f32, u32, vp, vp, vp, vp]
+        L.qo_dequantize_fixed_update.restype = C.c_int
         _lib = L
     return _lib
 
@@ -191,3 +199,40 @@ def apply_update(w_snap, zbar, zsum=None):
     zs = None if zsum is None else _f32(zsum).copy()
     lib().qo_apply_update(_p(w), _p(z), _p(u), _p(zs), w.size)
     return u, zs
+
+
+def epoch_commit(w, zsum, rounds):
+    """-> (w_next, zsum_reset): w + zsum / rounds, and the zeroed running sum."""
+    w = _f32(w).copy()
+    zs = _f32(zsum).copy()
+    lib().qo_epoch_commit(_p(w), _p(zs), int(rounds), w.size)
+    return w, zs
+
+
+def fixed_round(v, delta, b, r16):
+    return int(lib().qo_fixed_round(float(np.float32(v)), float(np.float32(delta)), int(b), int(r16)))
+
+
+def quantize_fixed(x, delta, b, seed, rnd, worker, center=None):
+    """Fixed-grid quantiser of Eq. (1)-(2): -> codes, ceil(d*b/32) uint32 words."""
+    x = _f32(x)
+    c = None if center is None else _f32(center)
+    codes = np.empty((x.size * b + 31) // 32, dtype=np.uint32)
+    rc = lib().qo_quantize_fixed(_p(x), _p(c), x.size, float(np.float32(delta)), int(b), int(seed), int(rnd),
+                                 int(worker), _p(codes))
+    if rc != 0:
+        raise ValueError("qo_quantize_fixed rejected its arguments")
+    return codes
+
+
+def dequantize_fixed_update(codes, d, delta, b, w_snap=None, zsum=None):
+    """-> (z, u or None, zsum_new or None)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint32)
+    z = np.empty(d, dtype=np.float32)
+    w = None if w_snap is None else _f32(w_snap)
+    u = None if w is None else np.empty(d, dtype=np.float32)
+    zs = None if zsum is None else _f32(zsum).copy()
+    rc = lib().qo_dequantize_fixed_update(_p(codes), int(d), float(np.float32(delta)), int(b), _p(w), _p(z), _p(u), _p(zs))
+    if rc != 0:
+        raise ValueError("qo_dequantize_fixed_update rejected its arguments")
+    return z, u, zs
