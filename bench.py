@@ -70,12 +70,91 @@ def load_traffic(workload):
     return None
 
 
+def bench_fixed_grid(args, cfg, torch, B, synth, dev):
+    """Server-to-worker direction with the quantiser as the paper writes it (Eq. (1)-(2), b = 8, the
+    paper's setting): one step = qesgd_quantize_fixed of a d-vector + qesgd_dequantize_fixed_update
+    (z, u = w + z, zsum += z)."""
+    import numpy as np
+    d, b = cfg.d, 8
+    x = synth.worker_vector(cfg, 0, dev)
+    w = synth.snapshot(cfg, dev)
+    delta = float(np.float32(4.0 * float(x.std()) / 128.0))      # range = 4 standard deviations
+    codes = torch.empty((d * b + 31) // 32, dtype=torch.int32, device=dev)
+    z = torch.empty(d, device=dev)
+    u = torch.empty(d, device=dev)
+    zsum = torch.zeros(d, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(r, ev=None):
+        if ev:
+            ev[0].record(stream)
+        B.qesgd_quantize_fixed(x, None, d, delta, b, cfg.seed, r, 0, codes, stream)
+        if ev:
+            ev[1].record(stream)
+        B.qesgd_dequantize_fixed_update(codes, d, delta, b, w, z, u, zsum, stream)
+        if ev:
+            ev[2].record(stream)
+
+    for r in range(args.warmup):
+        step(r)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for r in range(args.steps):
+        step(args.warmup + r, evs[r])
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    tq = sum(e[0].elapsed_time(e[1]) for e in evs) / len(evs)
+    td = sum(e[1].elapsed_time(e[2]) for e in evs) / len(evs)
+    cb = 4 * ((d * b + 31) // 32)
+    qb, db = 4 * d + cb, cb + 20 * d                               # read x, write codes | read codes, w, zsum; write z, u, zsum
+    out = {
+        "metric": "fixed-grid quantize and dequantize+update GB/s (fp32 params) and % of HBM peak",
+        "value": round((qb + db) / ms_step / 1e6, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} shape, fixed grid: d={d} ({cfg.model}), b={b}, delta={delta:.3e}, "
+                               f"entries {cfg.entries}, seed {cfg.seed}", "d": d, "b": b},
+        "phases": {
+            "quantize_fixed": {"algorithmic_bytes": qb, "ms_avg": round(tq, 4), "GBps": round(qb / tq / 1e6, 1),
+                               "frac_of_hbm_peak": round(qb / tq / 1e6 / HBM_PEAK_GBPS, 4),
+                               "params_per_s": round(d / tq * 1e3)},
+            "dequantize_fixed_update": {"algorithmic_bytes": db, "ms_avg": round(td, 4),
+                                        "GBps": round(db / td / 1e6, 1),
+                                        "frac_of_hbm_peak": round(db / td / 1e6 / HBM_PEAK_GBPS, 4),
+                                        "params_per_s": round(d / td * 1e3)}},
+    }
+    dom = "quantize_fixed" if tq >= td else "dequantize_fixed_update"
+    out["roofline"] = {"kernel": "k_" + dom, "bound": "hbm", "achieved": out["phases"][dom]["GBps"],
+                       "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": out["phases"][dom]["frac_of_hbm_peak"],
+                       "traffic": None}
+    if not args.no_cpu_baseline:
+        from oracle import qesgd_oracle as oracle
+        ds = min(d, 1 << 26)
+        xh, wh = x[:ds].cpu().numpy(), w[:ds].cpu().numpy()
+        t0 = time.perf_counter()
+        oc = oracle.quantize_fixed(xh, delta, b, cfg.seed, 0, 0)
+        t1 = time.perf_counter()
+        oracle.dequantize_fixed_update(oc, ds, delta, b, w_snap=wh, zsum=np.zeros(ds, np.float32))
+        t2 = time.perf_counter()
+        sb = 4 * ds + ds + ds + 20 * ds
+        out["cpu_baseline"] = {"value": round(sb / (t2 - t0) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {ds} of {d} coordinates, one step",
+                               "quantize_params_per_s": round(ds / (t1 - t0)),
+                               "dequantize_update_params_per_s": round(ds / (t2 - t1)),
+                               "seconds": round(t2 - t0, 2)}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default: the largest, VGG-16-sized)")
+    ap.add_argument("--path", default="qesgd", choices=["qesgd", "fixed"],
+                    help="qesgd: bucketed quantize-pack + unpack-aggregate-update (the headline path); "
+                         "fixed: the paper-literal fixed-grid quantiser (b = 8) + its fused inverse")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (reference point for --pmc byte counters)")
@@ -95,6 +174,8 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     cfg = synth.by_name(args.config)
+    if args.path == "fixed":
+        return bench_fixed_grid(args, cfg, torch, B, synth, dev)
     lay = B.qesgd_layout_query(cfg.d, cfg.s, cfg.bucket)
     slab = synth.worker_slab(cfg, dev)
     w = synth.snapshot(cfg, dev)

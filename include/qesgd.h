@@ -68,7 +68,10 @@ enum {
     QESGD_ERR_ALIGN = -7,      /* a pointer is not aligned as required                 */
     QESGD_ERR_STRIDE = -8,     /* a slab stride is too small or not a 16-byte multiple */
     QESGD_ERR_WORKSPACE = -9,  /* workspace NULL or smaller than qesgd_workspace_bytes */
-    QESGD_ERR_HIP = -10        /* a launch failed; see qesgd_last_hip_error()          */
+    QESGD_ERR_HIP = -10,       /* a launch failed; see qesgd_last_hip_error()          */
+    QESGD_ERR_BITS = -11,      /* b not in {2,4,8,16}                                  */
+    QESGD_ERR_DELTA = -12,     /* delta not a positive finite number                   */
+    QESGD_ERR_ROUNDS = -13     /* rounds == 0                                          */
 };
 
 enum { QESGD_NORM_L2 = 0, QESGD_NORM_MAX = 1 };
@@ -92,7 +95,7 @@ typedef struct qesgd_layout {
 int qesgd_layout_query(uint64_t d, uint32_t s, uint64_t bucket, qesgd_layout* out);
 
 /* Bytes of device scratch that qesgd_quantize_pack[_batched] needs for
- * (d, s, bucket, K).  0 whenever the zero-padded bucket has at most 65,536
+ * (d, s, bucket, K).  0 whenever the zero-padded bucket has at most 32,768
  * coordinates (the scale is then found in one pass over the input); larger
  * buckets take a second pass and park partial sums here.  Returns 0 on invalid
  * arguments as well (the quantize call reports them). */
@@ -142,6 +145,28 @@ int qesgd_unpack_aggregate_update(const void* packed_slab, uint64_t packed_strid
                                   uint64_t d, uint32_t s, uint64_t bucket,
                                   const float* w_snap, float* zbar_out, float* u_out,
                                   float* zsum_inout, void* stream);
+
+/* The quantiser exactly as the paper writes it (Sec. 2.1, Eq. (1)-(2)): fixed grid
+ * {delta*k : -2^(b-1) <= k <= 2^(b-1)-1}, b in {2,4,8,16}, step delta chosen by the caller
+ * (e.g. the schedule delta_t = O(1/(sqrt(t) 2^(b-1))) of Sec. 4).  Per coordinate:
+ * a = fl(v/delta); a >= 2^(b-1)-1 gives the top code, a <= -2^(b-1) the bottom code (the two
+ * clamp cases); otherwise k = floor(a) + [r + trunc(fl(a - floor(a))*2^16) >= 2^16] with the same
+ * variates r as qesgd_quantize_pack.  v = x, or x - center when center is given.
+ *   codes  device, 16-byte aligned, ceil(d*b/32) uint32 words, written: coordinate i is the
+ *          b-bit two's complement of k at bit (i*b)&31 of word (i*b)>>5; unused high bits 0. */
+int qesgd_quantize_fixed(const float* x, const float* center, uint64_t d, float delta, uint32_t b,
+                         uint64_t seed, uint32_t round, uint32_t worker, void* codes, void* stream);
+
+/* Inverse of the above fused with Alg. 2's u = w_t + z: z_i = fl(k_i * delta),
+ * u_i = w_i + z_i, zsum_i += z_i.  z_out, (w_snap, u_out) and zsum_inout are each optional
+ * (NULL), at least one output must be given; u_out needs w_snap. */
+int qesgd_dequantize_fixed_update(const void* codes, uint64_t d, float delta, uint32_t b,
+                                  const float* w_snap, float* z_out, float* u_out, float* zsum_inout,
+                                  void* stream);
+
+/* End of an epoch (Alg. 3, last step; equal to Alg. 2's mean of the iterates u_{t,k}):
+ * w_i += zsum_i / rounds, then zsum_i = 0 for the next epoch (z starts again at 0). */
+int qesgd_epoch_commit(float* w_inout, float* zsum_inout, uint32_t rounds, uint64_t d, void* stream);
 
 const char* qesgd_strerror(int code);
 /* hipError_t (as int) of the last failed launch on the calling thread, 0 if none. */

@@ -23,6 +23,7 @@ NORM_MAX = 1
 OK = 0
 ERR_NULL, ERR_DIM, ERR_LEVELS, ERR_BUCKET, ERR_WORKERS = -1, -2, -3, -4, -5
 ERR_NORM_KIND, ERR_ALIGN, ERR_STRIDE, ERR_WORKSPACE, ERR_HIP = -6, -7, -8, -9, -10
+ERR_BITS, ERR_DELTA, ERR_ROUNDS = -11, -12, -13
 
 
 class QesgdError(RuntimeError):
@@ -78,6 +79,12 @@ def lib():
         L.qesgd_apply_update.restype = C.c_int
         L.qesgd_unpack_aggregate_update.argtypes = [vp, u64, u32, u64, u32, u64, vp, vp, vp, vp, vp]
         L.qesgd_unpack_aggregate_update.restype = C.c_int
+        L.qesgd_quantize_fixed.argtypes = [vp, vp, u64, C.c_float, u32, u64, u32, u32, vp, vp]
+        L.qesgd_quantize_fixed.restype = C.c_int
+        L.qesgd_dequantize_fixed_update.argtypes = [vp, u64, C.c_float, u32, vp, vp, vp, vp, vp]
+        L.qesgd_dequantize_fixed_update.restype = C.c_int
+        L.qesgd_epoch_commit.argtypes = [vp, vp, u32, u64, vp]
+        L.qesgd_epoch_commit.restype = C.c_int
         L.qesgd_strerror.argtypes = [C.c_int]
         L.qesgd_strerror.restype = C.c_char_p
         L.qesgd_last_hip_error.argtypes = []
@@ -154,6 +161,22 @@ def qesgd_unpack_aggregate_update(packed_slab, packed_stride, K, d, s, bucket, w
                                                int(s), int(bucket), _ptr(w_snap), _ptr(zbar_out),
                                                _ptr(u_out), _ptr(zsum_inout), _stream(stream)),
            "qesgd_unpack_aggregate_update")
+
+
+def qesgd_quantize_fixed(x, center, d, delta, b, seed, rnd, worker, codes, stream=None):
+    _check(lib().qesgd_quantize_fixed(_ptr(x), _ptr(center), int(d), float(delta), int(b), int(seed), int(rnd),
+                                      int(worker), _ptr(codes), _stream(stream)), "qesgd_quantize_fixed")
+
+
+def qesgd_dequantize_fixed_update(codes, d, delta, b, w_snap, z_out, u_out, zsum_inout, stream=None):
+    _check(lib().qesgd_dequantize_fixed_update(_ptr(codes), int(d), float(delta), int(b), _ptr(w_snap), _ptr(z_out),
+                                               _ptr(u_out), _ptr(zsum_inout), _stream(stream)),
+           "qesgd_dequantize_fixed_update")
+
+
+def qesgd_epoch_commit(w_inout, zsum_inout, rounds, d, stream=None):
+    _check(lib().qesgd_epoch_commit(_ptr(w_inout), _ptr(zsum_inout), int(rounds), int(d), _stream(stream)),
+           "qesgd_epoch_commit")
 
 
 def qesgd_abi_version() -> int:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqesgd.so")
-SOURCES = ["qesgd_api.cpp", "qesgd_quantize.hip", "qesgd_aggregate.hip"]
+SOURCES = ["qesgd_api.cpp", "qesgd_quantize.hip", "qesgd_aggregate.hip", "qesgd_fixed.hip"]
 
 # -ffp-contract=off: the results are defined without fused multiply-add.
 # packed-fp32 ops are switched off for this toolchain/hardware combination.

@@ -178,6 +178,40 @@ int qesgd_unpack_aggregate_update(const void* packed_slab, uint64_t packed_strid
                             zsum_inout, true, stream);
 }
 
+static bool fixed_bits_ok(uint32_t b) { return b == 2 || b == 4 || b == 8 || b == 16; }
+
+int qesgd_quantize_fixed(const float* x, const float* center, uint64_t d, float delta, uint32_t b,
+                         uint64_t seed, uint32_t round, uint32_t worker, void* codes, void* stream) {
+    if (!x || !codes) return QESGD_ERR_NULL;
+    if (d == 0 || d >= (1ull << 40)) return QESGD_ERR_DIM;
+    if (!fixed_bits_ok(b)) return QESGD_ERR_BITS;
+    if (!(delta > 0.0f) || !(delta < __builtin_inff())) return QESGD_ERR_DELTA;
+    if (!aligned(x, 16) || !aligned(center, 16) || !aligned(codes, 16)) return QESGD_ERR_ALIGN;
+    return launch_quantize_fixed(x, center, d, delta, b, seed, round, worker, codes, (hipStream_t)stream);
+}
+
+int qesgd_dequantize_fixed_update(const void* codes, uint64_t d, float delta, uint32_t b,
+                                  const float* w_snap, float* z_out, float* u_out, float* zsum_inout,
+                                  void* stream) {
+    if (!codes || (!z_out && !u_out && !zsum_inout)) return QESGD_ERR_NULL;
+    if ((u_out != nullptr) != (w_snap != nullptr)) return QESGD_ERR_NULL;
+    if (d == 0 || d >= (1ull << 40)) return QESGD_ERR_DIM;
+    if (!fixed_bits_ok(b)) return QESGD_ERR_BITS;
+    if (!(delta > 0.0f) || !(delta < __builtin_inff())) return QESGD_ERR_DELTA;
+    if (!aligned(codes, 16) || !aligned(w_snap, 16) || !aligned(z_out, 16) || !aligned(u_out, 16) ||
+        !aligned(zsum_inout, 16))
+        return QESGD_ERR_ALIGN;
+    return launch_dequantize_fixed_update(codes, d, delta, b, w_snap, z_out, u_out, zsum_inout, (hipStream_t)stream);
+}
+
+int qesgd_epoch_commit(float* w_inout, float* zsum_inout, uint32_t rounds, uint64_t d, void* stream) {
+    if (!w_inout || !zsum_inout) return QESGD_ERR_NULL;
+    if (d == 0 || d >= (1ull << 40)) return QESGD_ERR_DIM;
+    if (rounds == 0) return QESGD_ERR_ROUNDS;
+    if (!aligned(w_inout, 16) || !aligned(zsum_inout, 16)) return QESGD_ERR_ALIGN;
+    return launch_epoch_commit(w_inout, zsum_inout, rounds, d, (hipStream_t)stream);
+}
+
 const char* qesgd_strerror(int code) {
     switch (code) {
         case QESGD_OK: return "ok";
@@ -191,6 +225,9 @@ const char* qesgd_strerror(int code) {
         case QESGD_ERR_STRIDE: return "slab stride too small or not a multiple of 16 bytes (packed: 256)";
         case QESGD_ERR_WORKSPACE: return "workspace missing or smaller than qesgd_workspace_bytes()";
         case QESGD_ERR_HIP: return "kernel launch failed (see qesgd_last_hip_error)";
+        case QESGD_ERR_BITS: return "b must be one of 2, 4, 8, 16";
+        case QESGD_ERR_DELTA: return "delta must be a positive finite number";
+        case QESGD_ERR_ROUNDS: return "rounds must be at least 1";
         default: return "unknown error code";
     }
 }

@@ -65,6 +65,12 @@ int launch_aggregate(const Shape& sh, const AggregateArgs& a);
 int launch_apply_update(const float* w, const float* zbar, float* u, float* zsum, uint64_t d,
                         hipStream_t stream);
 
+int launch_quantize_fixed(const float* x, const float* center, uint64_t d, float delta, uint32_t b,
+                          uint64_t seed, uint32_t round, uint32_t worker, void* codes, hipStream_t stream);
+int launch_dequantize_fixed_update(const void* codes, uint64_t d, float delta, uint32_t b, const float* w,
+                                   float* z, float* u, float* zsum, hipStream_t stream);
+int launch_epoch_commit(float* w, float* zsum, uint32_t rounds, uint64_t d, hipStream_t stream);
+
 void set_last_hip_error(int e);
 
 }  // namespace qesgd

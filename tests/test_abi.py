@@ -136,3 +136,30 @@ def test_missing_library_is_loud(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libqesgd.so")
     with pytest.raises(RuntimeError, match="not found"):
         binding.qesgd_layout_query(10, 4, 32)
+
+
+def test_fixed_grid_and_epoch_commit_argument_errors(B):
+    L = B.lib()
+    x, c, w, z, u, zs = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x60000
+    assert L.qesgd_quantize_fixed(None, None, 100, 0.1, 8, 1, 0, 0, c, None) == B.ERR_NULL
+    assert L.qesgd_quantize_fixed(x, None, 100, 0.1, 8, 1, 0, 0, None, None) == B.ERR_NULL
+    assert L.qesgd_quantize_fixed(x, None, 0, 0.1, 8, 1, 0, 0, c, None) == B.ERR_DIM
+    assert L.qesgd_quantize_fixed(x, None, 100, 0.1, 3, 1, 0, 0, c, None) == B.ERR_BITS
+    assert L.qesgd_quantize_fixed(x, None, 100, 0.1, 32, 1, 0, 0, c, None) == B.ERR_BITS
+    assert L.qesgd_quantize_fixed(x, None, 100, 0.0, 8, 1, 0, 0, c, None) == B.ERR_DELTA
+    assert L.qesgd_quantize_fixed(x, None, 100, -1.0, 8, 1, 0, 0, c, None) == B.ERR_DELTA
+    assert L.qesgd_quantize_fixed(x, None, 100, float("inf"), 8, 1, 0, 0, c, None) == B.ERR_DELTA
+    assert L.qesgd_quantize_fixed(x, None, 100, float("nan"), 8, 1, 0, 0, c, None) == B.ERR_DELTA
+    assert L.qesgd_quantize_fixed(x + 4, None, 100, 0.1, 8, 1, 0, 0, c, None) == B.ERR_ALIGN
+    assert L.qesgd_dequantize_fixed_update(None, 100, 0.1, 8, w, z, u, zs, None) == B.ERR_NULL
+    assert L.qesgd_dequantize_fixed_update(c, 100, 0.1, 8, None, None, None, None, None) == B.ERR_NULL
+    assert L.qesgd_dequantize_fixed_update(c, 100, 0.1, 8, None, z, u, None, None) == B.ERR_NULL   # u needs w
+    assert L.qesgd_dequantize_fixed_update(c, 100, 0.1, 5, w, z, u, zs, None) == B.ERR_BITS
+    assert L.qesgd_dequantize_fixed_update(c, 100, 0.0, 8, w, z, u, zs, None) == B.ERR_DELTA
+    assert L.qesgd_dequantize_fixed_update(c, 100, 0.1, 8, w, z + 8, u, zs, None) == B.ERR_ALIGN
+    assert L.qesgd_epoch_commit(None, zs, 3, 100, None) == B.ERR_NULL
+    assert L.qesgd_epoch_commit(w, zs, 0, 100, None) == B.ERR_ROUNDS
+    assert L.qesgd_epoch_commit(w, zs, 3, 0, None) == B.ERR_DIM
+    assert L.qesgd_epoch_commit(w, zs + 4, 3, 100, None) == B.ERR_ALIGN
+    for code in (B.ERR_BITS, B.ERR_DELTA, B.ERR_ROUNDS):
+        assert "unknown" not in B.strerror(code)
