@@ -1,0 +1,66 @@
+"""More shapes through the specialised quantize kernel: every power-of-two bucket from 32 to 32768,
+every level width, vectors that are an exact multiple of the tile, smaller than a tile, and one
+coordinate longer; 64 workers in one launch."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1901_03040_amd import binding
+    assert torch.cuda.is_available()
+    binding.lib()
+    return binding
+
+
+def run_and_compare(oracle, B, x, s, bucket, seed, rnd, K=1, center=None, d=None):
+    d = x.shape[-1] if d is None else d
+    lay = B.qesgd_layout_query(d, s, bucket)
+    packed = B.alloc_packed(lay, K)
+    packed.fill_(0xA5)
+    if K == 1:
+        B.qesgd_quantize_pack(x, center, d, s, bucket, 0, seed, rnd, 0, packed)
+    else:
+        B.qesgd_quantize_pack_batched(x, x.stride(0), center, d, s, bucket, 0, seed, rnd, K, packed, packed.stride(0))
+    torch.cuda.synchronize()
+    xh = x.cpu().numpy().reshape(K, -1)
+    ch = None if center is None else center.cpu().numpy()
+    assert np.isfinite(xh).all() and (ch is None or np.isfinite(ch).all()), "inputs changed on the device"
+    for k in range(K):
+        n, sg, lv = B.planes(packed[k], lay)
+        on, osw, olw = oracle.quantize_pack(xh[k, :d], s, bucket, seed, rnd, k, center=ch)
+        assert np.array_equal(n.cpu().numpy().view(np.uint32), on.view(np.uint32)), (k, "norms")
+        assert np.array_equal(sg.cpu().numpy().view(np.uint32), osw), (k, "signs")
+        assert np.array_equal(lv.cpu().numpy().view(np.uint32), olw), (k, "levels")
+
+
+@pytest.mark.parametrize("log2n", range(5, 16))
+@pytest.mark.parametrize("s", [2, 4, 16, 256, 65536])
+def test_every_power_of_two_bucket(oracle, B, log2n, s):
+    bucket = 1 << log2n
+    tile = max(4096, bucket)
+    g = torch.Generator(device="cpu").manual_seed(log2n * 100 + s)
+    for d in (3 * tile, 2 * tile + bucket + 37):          # whole tiles only; tiles + a ragged tail
+        x = (torch.randn(d, generator=g) * 1e-2).cuda()
+        run_and_compare(oracle, B, x, s, bucket, 99, log2n)
+
+
+@pytest.mark.parametrize("d", [4095, 4096, 4097, 8191, 8192, 12288 + 8])
+def test_around_one_tile(oracle, B, d):
+    g = torch.Generator(device="cpu").manual_seed(d)
+    x = (torch.randn(d, generator=g) * 1e-2).cuda()
+    for bucket in (128, 4096):
+        run_and_compare(oracle, B, x, 16, bucket, 5, 1)
+
+
+def test_sixty_four_workers_with_center(oracle, B):
+    d, K = 10_000, 64
+    g = torch.Generator(device="cpu").manual_seed(1)
+    stride = (d + 63) // 64 * 64
+    slab = torch.zeros(K, stride)
+    slab[:, :d] = torch.randn(K, d, generator=g) * 1e-3
+    c = torch.randn(d, generator=g) * 1e-3
+    run_and_compare(oracle, B, slab.cuda(), 4, 1024, 3, 9, K=K, center=c.cuda(), d=d)
