@@ -38,7 +38,9 @@ struct QParams {
     uint32_t log2N;
     uint32_t tile0;              // generic kernel: first tile it covers
     uint32_t tiles_per_worker;   // generic kernel: tiles it covers per worker
-    uint32_t full_tiles;         // fast kernel: tiles per worker
+    uint32_t full_tiles;         // fast kernels: tiles per worker
+    uint32_t ws_tiles_per_worker;  // partial sums: workspace entries per worker (nb * N / 4096)
+    uint64_t data_tiles;         // partial sums: 4096-slot tiles of a worker that hold coordinates
     uint32_t key0, key1;
     uint32_t round;
     uint32_t worker0;
@@ -373,6 +375,54 @@ __global__ void __launch_bounds__(Geo<LOG2N>::NW * 64) k_quantize_pack_fast(cons
     process_tile<M, LOG2N>(cx, buf, t, sm);
 }
 
+// Buckets wider than kMaxSinglePassBucket, tiles wholly inside the vector (slot == coordinate:
+// power-of-two bucket, or a single bucket).  First pass: tree sum of one 4096-coordinate tile into
+// the workspace.  Last pass: the quantiser with the bucket scale read from the norms plane; a tile
+// never straddles two such buckets, so the scale is one scalar per workgroup.
+template <bool CENTER>
+__global__ void __launch_bounds__(256) k_tile_partials_fast(const QParams p) {
+    constexpr int KIND = QESGD_NORM_L2;
+    __shared__ float sm[4];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t k = blockIdx.x / p.full_tiles;
+    const uint32_t t = blockIdx.x - k * p.full_tiles;
+    const uint32_t lane_off = wave * (2u * kChunk) + lane * kLaneElems;
+    float v[2][8];
+    load_tile<2, CENTER>(p.x + (uint64_t)k * p.x_stride + (uint64_t)t * kPartialTile,
+                         p.center + (uint64_t)t * kPartialTile, lane_off, v);
+    const float t0 = lane_butterfly<KIND>(lane_tree<KIND>(v[0]), 64);
+    const float t1 = lane_butterfly<KIND>(lane_tree<KIND>(v[1]), 64);
+    if (lane == 0) sm[wave] = t0 + t1;
+    __syncthreads();
+    if (threadIdx.x == 0) p.workspace[(uint64_t)k * p.ws_tiles_per_worker + t] = (sm[0] + sm[1]) + (sm[2] + sm[3]);
+}
+
+template <int M, bool CENTER>
+__global__ void __launch_bounds__(256) k_quantize_pack_pre_fast(const QParams p) {
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t k = blockIdx.x / p.full_tiles;
+    const uint32_t t = blockIdx.x - k * p.full_tiles;
+    unsigned char* __restrict__ out = p.packed + (uint64_t)k * p.packed_stride;
+    const float* __restrict__ norms = reinterpret_cast<const float*>(out + p.norms_off);
+    uint32_t* __restrict__ signs = reinterpret_cast<uint32_t*>(out + p.signs_off);
+    uint32_t* __restrict__ levels = reinterpret_cast<uint32_t*>(out + p.levels_off);
+    const uint32_t lane_off = wave * (2u * kChunk) + lane * kLaneElems;
+    const uint64_t e0 = (uint64_t)t * kPartialTile;
+    float v[2][8];
+    load_tile<2, CENTER>(p.x + (uint64_t)k * p.x_stride + e0, p.center + e0, lane_off, v);
+    const float inv = inverse_step(norms[e0 >> p.log2N], p.smax);
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const uint64_t i = e0 + lane_off + (uint32_t)c * kChunk;
+        const uint64_t g = i >> 3;
+        uint32_t rnd[4];
+        philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), p.worker0 + k, p.round, p.key0, p.key1, rnd);
+        uint32_t sign_byte, bits[4];
+        round_and_pack<M>(v[c], rnd, inv, p.smax, sign_byte, bits);
+        store_codes<M>(signs, levels, i, 8u, lane, sign_byte, bits);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Generic kernel.
 // ---------------------------------------------------------------------------
@@ -504,9 +554,9 @@ __global__ void k_quantize_pack(const QParams p) {
 }
 
 // ---------------------------------------------------------------------------
-// Buckets wider than kMaxSinglePassBucket: pass A leaves the tree sum of every
-// 4096-slot tile in the workspace, pass B finishes the tree per bucket and
-// writes the scale, then k_quantize_pack<.., PRE = true> reads it.
+// Buckets wider than kMaxSinglePassBucket, guarded versions: pass A leaves the
+// tree sum of a 4096-slot tile in the workspace, pass B finishes the tree per
+// bucket and writes the scale, then k_quantize_pack<.., PRE = true> reads it.
 // workspace[(k*nb + b)*P + t], P = N / 4096.
 // ---------------------------------------------------------------------------
 template <int KIND>
@@ -516,7 +566,7 @@ __global__ void k_tile_partials(const QParams p) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
     const uint32_t k = blockIdx.x / p.tiles_per_worker;
-    const uint32_t tile = blockIdx.x - k * p.tiles_per_worker;
+    const uint32_t tile = p.tile0 + (blockIdx.x - k * p.tiles_per_worker);
     const float* __restrict__ x = p.x + (uint64_t)k * p.x_stride;
     const uint64_t slot0 = ((uint64_t)tile * 4 + wave) * (uint64_t)(CH * kChunk) + lane * kLaneElems;
     float t[CH];
@@ -533,19 +583,29 @@ __global__ void k_tile_partials(const QParams p) {
     if (threadIdx.x == 0) {
         const float total = combine<KIND>(combine<KIND>(sm[0], sm[1]), combine<KIND>(sm[2], sm[3]));
         // tiles of a bucket are consecutive in slot space, so (bucket, tile in bucket) = tile index
-        p.workspace[(uint64_t)k * p.tiles_per_worker + tile] = total;
+        p.workspace[(uint64_t)k * p.ws_tiles_per_worker + tile] = total;
     }
 }
 
+// Finishes the tree of one bucket in place: P leaves, of which only the first `valid` were
+// written (the rest of the padded bucket is +0 and is never read: a node that starts at or
+// beyond `valid` is 0, the identity of both combines).
 template <int KIND>
-__global__ void k_finish_norms(const QParams p, uint64_t P) {
+__global__ void k_finish_norms(const QParams p, uint64_t P, uint32_t dense) {
     const uint64_t kb = blockIdx.x;                     // k*nb + b
     const uint32_t k = (uint32_t)(kb / p.nb);
     const uint64_t b = kb - (uint64_t)k * p.nb;
     float* ws = p.workspace + kb * P;
+    uint64_t valid = P;
+    if (dense) {
+        const uint64_t left = p.data_tiles - b * P;     // buckets before the last are full
+        valid = left < P ? left : P;
+    }
     for (uint64_t h = 1; h < P; h <<= 1) {
-        for (uint64_t r = (uint64_t)threadIdx.x * 2 * h; r < P; r += (uint64_t)blockDim.x * 2 * h)
-            ws[r] = combine<KIND>(ws[r], ws[r + h]);
+        for (uint64_t r = (uint64_t)threadIdx.x * 2 * h; r < valid; r += (uint64_t)blockDim.x * 2 * h) {
+            const float other = (r + h < valid) ? ws[r + h] : 0.0f;
+            ws[r] = combine<KIND>(ws[r], other);
+        }
         __syncthreads();
     }
     if (threadIdx.x == 0) {
@@ -611,6 +671,22 @@ void launch_fast(const QParams& p, uint32_t m, uint32_t blocks, hipStream_t st) 
     }
 }
 
+template <int M>
+void launch_pre_fast_m(const QParams& p, uint32_t blocks, hipStream_t st) {
+    if (p.center) hipLaunchKernelGGL((k_quantize_pack_pre_fast<M, true>), dim3(blocks), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL((k_quantize_pack_pre_fast<M, false>), dim3(blocks), dim3(256), 0, st, p);
+}
+
+void launch_pre_fast(const QParams& p, uint32_t m, uint32_t blocks, hipStream_t st) {
+    switch (m) {
+        case 1: launch_pre_fast_m<1>(p, blocks, st); break;
+        case 2: launch_pre_fast_m<2>(p, blocks, st); break;
+        case 4: launch_pre_fast_m<4>(p, blocks, st); break;
+        case 8: launch_pre_fast_m<8>(p, blocks, st); break;
+        default: launch_pre_fast_m<16>(p, blocks, st); break;
+    }
+}
+
 int check_launch() {
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -657,20 +733,39 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
     const dim3 block(nwaves * kWaveSize);
 
     if (two_pass) {
-        p.tile0 = 0;
-        p.tiles_per_worker = (uint32_t)tiles;
-        const dim3 grid((uint32_t)(tiles * a.K));
+        // Slot space equals coordinate space when the bucket is a power of two or there is a single
+        // bucket; then only the tiles that hold coordinates are visited, and the ones wholly inside
+        // the vector take the unguarded kernels.
         const uint64_t P = sh.N / kPartialTile;          // tiles == nb * P
-        if (a.norm_kind == QESGD_NORM_L2) {
-            hipLaunchKernelGGL(k_tile_partials<QESGD_NORM_L2>, grid, block, 0, a.stream, p);
-            hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_L2>, dim3((uint32_t)(sh.nb * a.K)), dim3(256), 0, a.stream, p, P);
-        } else {
-            hipLaunchKernelGGL(k_tile_partials<QESGD_NORM_MAX>, grid, block, 0, a.stream, p);
-            hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_MAX>, dim3((uint32_t)(sh.nb * a.K)), dim3(256), 0, a.stream, p, P);
+        const bool dense = sh.N == sh.B || sh.nb == 1;
+        const uint64_t data_tiles = dense ? (sh.d + kPartialTile - 1) / kPartialTile : tiles;
+        const uint64_t full_tiles = (dense && a.norm_kind == QESGD_NORM_L2) ? sh.d / kPartialTile : 0;
+        p.ws_tiles_per_worker = (uint32_t)tiles;
+        p.data_tiles = data_tiles;
+        p.full_tiles = (uint32_t)full_tiles;
+        p.tile0 = (uint32_t)full_tiles;
+        p.tiles_per_worker = (uint32_t)(data_tiles - full_tiles);
+        const dim3 fast_grid((uint32_t)(full_tiles * a.K)), tail_grid((uint32_t)((data_tiles - full_tiles) * a.K));
+        if (full_tiles > 0) {
+            if (p.center) hipLaunchKernelGGL(k_tile_partials_fast<true>, fast_grid, block, 0, a.stream, p);
+            else hipLaunchKernelGGL(k_tile_partials_fast<false>, fast_grid, block, 0, a.stream, p);
         }
-        const int rc = check_launch();
+        const dim3 finish_grid((uint32_t)(sh.nb * a.K));
+        if (a.norm_kind == QESGD_NORM_L2) {
+            if (data_tiles > full_tiles) hipLaunchKernelGGL(k_tile_partials<QESGD_NORM_L2>, tail_grid, block, 0, a.stream, p);
+            hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_L2>, finish_grid, dim3(256), 0, a.stream, p, P, dense ? 1u : 0u);
+        } else {
+            if (data_tiles > full_tiles) hipLaunchKernelGGL(k_tile_partials<QESGD_NORM_MAX>, tail_grid, block, 0, a.stream, p);
+            hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_MAX>, finish_grid, dim3(256), 0, a.stream, p, P, dense ? 1u : 0u);
+        }
+        int rc = check_launch();
         if (rc != QESGD_OK) return rc;
-        launch_m<2, true>(p, sh.m, a.norm_kind, grid, block, a.stream);
+        if (full_tiles > 0) {
+            launch_pre_fast(p, sh.m, (uint32_t)(full_tiles * a.K), a.stream);
+            rc = check_launch();
+            if (rc != QESGD_OK) return rc;
+        }
+        if (data_tiles > full_tiles) launch_m<2, true>(p, sh.m, a.norm_kind, tail_grid, block, a.stream);
         return check_launch();
     }
 

@@ -69,7 +69,7 @@ def rel_err(got, want):
 @pytest.mark.parametrize("d,bucket", [
     (20_000, 512), (20_010, 2048), (33_001, 4096), (70_003, 8192), (70_003, 16_384),
     (100_007, 32_768), (5_000, 32), (5_003, 64), (9_999, 96), (9_000, 1_000_000), (40_000, 40_000),
-    (100_000, 100_000), (300_001, 131_072 * 2)])
+    (100_000, 100_000), (300_001, 131_072 * 2), (200_003, 48_000), (150_000, 65_536)])
 def test_quantize_pack_matches_oracle(oracle, B, s, d, bucket):
     g = torch.Generator(device="cpu").manual_seed(d * 31 + s)
     x = (torch.randn(d, generator=g) * 1e-3).to(torch.float32)
