@@ -236,7 +236,7 @@ def main():
 
     def roofline(name):
         ph = phases[name]
-        launches = {"quantize_pack": "k_quantize_pack_fast (+ guarded k_quantize_pack for the ragged last tile)",
+        launches = {"quantize_pack": "k_quantize_pack_fast",
                     "unpack_aggregate_update": "k_unpack_aggregate_update"}[name]
         return {"kernel": launches, "bound": "hbm", "achieved": ph["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": ph["frac_of_hbm_peak"], "traffic": traffic.get(name)}

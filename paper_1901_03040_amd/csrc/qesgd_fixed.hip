@@ -3,33 +3,11 @@
 // range, stochastic floor/ceil inside; its inverse fused with u = w_t + z (Alg. 2); and the
 // end-of-epoch commit w_{t+1} = w_t + (1/K_t) sum_k z_{t,k} (Alg. 3, last step).
 // No reduction is needed, so these are plain streaming kernels.
+#include "qesgd_device.h"
 #include "qesgd_internal.h"
 
 namespace qesgd {
 namespace {
-
-__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
-    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
-}
-
-// Philox4x32-10 (Salmon et al., SC'11); the key schedule is wave-uniform.
-__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                              uint32_t k0, uint32_t k1, uint32_t (&o)[4]) {
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const uint64_t pa = (uint64_t)0xD2511F53u * c0;
-        const uint64_t pb = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = xor3((uint32_t)(pb >> 32), c1, k0);
-        const uint32_t n2 = xor3((uint32_t)(pa >> 32), c3, k1);
-        c1 = (uint32_t)pb;
-        c3 = (uint32_t)pa;
-        c0 = n0;
-        c2 = n2;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    o[0] = c0; o[1] = c1; o[2] = c2; o[3] = c3;
-}
 
 struct FParams {
     const float* x;
@@ -94,8 +72,7 @@ __global__ void __launch_bounds__(256) k_quantize_fixed(const FParams p) {
     uint32_t code[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        const uint32_t word = rnd[e >> 1];
-        const uint32_t r16 = (e & 1) ? (word >> 16) : (word & 0xFFFFu);
+        const uint32_t r16 = variate16(rnd, e);
         const int32_t k = fixed_round(v[e], p.delta, p.lo, p.hi, r16);
         code[e] = ((uint32_t)e < nvalid) ? ((uint32_t)k & mask) : 0u;     // padding bits stay 0
     }

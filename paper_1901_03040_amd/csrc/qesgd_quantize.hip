@@ -19,6 +19,7 @@
 //   k_quantize_pack       everything else: ragged last tile, buckets that are
 //                         not a power of two, max-norm, tiny vectors, and the
 //                         second pass of buckets too wide for one workgroup.
+#include "qesgd_device.h"
 #include "qesgd_internal.h"
 
 namespace qesgd {
@@ -38,7 +39,8 @@ struct QParams {
     uint32_t log2N;
     uint32_t tile0;              // generic kernel: first tile it covers
     uint32_t tiles_per_worker;   // generic kernel: tiles it covers per worker
-    uint32_t full_tiles;         // fast kernels: tiles per worker
+    uint32_t full_tiles;         // fast kernels: tiles per worker that lie wholly inside the vector
+    uint32_t tail_tiles;         // fast quantize kernel: ragged tiles per worker after those (0 or 1)
     uint32_t ws_tiles_per_worker;  // partial sums: workspace entries per worker (nb * N / 4096)
     uint64_t data_tiles;         // partial sums: 4096-slot tiles of a worker that hold coordinates
     uint32_t key0, key1;
@@ -47,31 +49,6 @@ struct QParams {
     float smax;
 };
 
-// ---------------------------------------------------------------------------
-// Philox4x32-10 (Salmon et al., SC'11).  The key is wave-uniform, so its Weyl
-// sequence lives in scalar registers; the three-way xor is one v_bitop3.
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
-    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
-}
-
-__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                              uint32_t k0, uint32_t k1, uint32_t (&o)[4]) {
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const uint64_t pa = (uint64_t)0xD2511F53u * c0;
-        const uint64_t pb = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = xor3((uint32_t)(pb >> 32), c1, k0);
-        const uint32_t n2 = xor3((uint32_t)(pa >> 32), c3, k1);
-        c1 = (uint32_t)pb;
-        c3 = (uint32_t)pa;
-        c0 = n0;
-        c2 = n2;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    o[0] = c0; o[1] = c1; o[2] = c2; o[3] = c3;
-}
 
 // ---------------------------------------------------------------------------
 // Cross-lane helpers.
@@ -170,15 +147,13 @@ __device__ __forceinline__ void round_and_pack(const float (&v)[8], const uint32
         const float smax16 = smax * 65536.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const uint32_t word = rnd[e >> 1];
-            const uint32_t r16 = (e & 1) ? (word >> 16) : (word & 0xFFFFu);
+            const uint32_t r16 = variate16(rnd, e);
             y[e] = (uint32_t)fminf(fabsf(v[e]) * inv16, smax16) + r16;
         }
     } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const uint32_t word = rnd[e >> 1];
-            const uint32_t r16 = (e & 1) ? (word >> 16) : (word & 0xFFFFu);
+            const uint32_t r16 = variate16(rnd, e);
             y[e] = (uint32_t)(fminf(fabsf(v[e]) * inv, smax) * 65536.0f) + r16;
         }
     }
@@ -250,6 +225,141 @@ __device__ __forceinline__ void store_codes(uint32_t* __restrict__ sign_words, u
             if (nvalid > 6) level_words[(i >> 1) + 3] = bits[3];
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// Guarded tile: the shared body of the generic kernel and of the ragged last tile.
+// ---------------------------------------------------------------------------
+// Where the 8 slots of this lane fall: bucket, first coordinate, how many of
+// them are real coordinates (0..8), and whether they open the bucket.
+struct LaneSpan {
+    uint64_t bucket;
+    uint64_t i;        // first coordinate (a multiple of 8)
+    uint32_t nvalid;
+    bool opens_bucket;
+};
+
+__device__ __forceinline__ LaneSpan lane_span(uint64_t slot, const QParams& p) {
+    LaneSpan s;
+    const uint64_t N = 1ull << p.log2N;
+    s.bucket = slot >> p.log2N;
+    const uint64_t j = slot & (N - 1);
+    uint64_t len = 0;
+    if (s.bucket < p.nb) {
+        const uint64_t rem = p.d - s.bucket * p.B;
+        len = rem < p.B ? rem : p.B;
+    }
+    s.nvalid = j < len ? (uint32_t)((len - j) < 8 ? (len - j) : 8) : 0u;
+    s.i = s.bucket * p.B + j;
+    s.opens_bucket = (j == 0) && (s.bucket < p.nb);
+    return s;
+}
+
+__device__ __forceinline__ void load_lane(const float* __restrict__ x, const float* __restrict__ center,
+                                          const LaneSpan& s, float (&v)[8]) {
+    if (s.nvalid == 8) {
+        const float4 a = *reinterpret_cast<const float4*>(x + s.i);
+        const float4 b = *reinterpret_cast<const float4*>(x + s.i + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        if (center) {
+            const float4 ca = *reinterpret_cast<const float4*>(center + s.i);
+            const float4 cb = *reinterpret_cast<const float4*>(center + s.i + 4);
+            v[0] -= ca.x; v[1] -= ca.y; v[2] -= ca.z; v[3] -= ca.w;
+            v[4] -= cb.x; v[5] -= cb.y; v[6] -= cb.z; v[7] -= cb.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float t = 0.0f;
+            if ((uint32_t)e < s.nvalid) {
+                t = x[s.i + e];
+                if (center) t -= center[s.i + e];
+            }
+            v[e] = t;
+        }
+    }
+}
+
+// One tile of worker k with every access guarded per lane.  PRE = true: the scales were
+// computed by the partial-sum passes and are read from the norms plane.  sm: 32 floats of LDS.
+template <int M, int CH, int KIND, bool PRE>
+__device__ __forceinline__ void guarded_tile(const QParams& p, uint32_t k, uint32_t tile, float* sm) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t nwaves = blockDim.x >> 6;
+    const float* __restrict__ x = p.x + (uint64_t)k * p.x_stride;
+    unsigned char* __restrict__ out = p.packed + (uint64_t)k * p.packed_stride;
+    float* __restrict__ norms = reinterpret_cast<float*>(out + p.norms_off);
+    uint32_t* __restrict__ signs = reinterpret_cast<uint32_t*>(out + p.signs_off);
+    uint32_t* __restrict__ levels = reinterpret_cast<uint32_t*>(out + p.levels_off);
+    const uint64_t N = 1ull << p.log2N;
+    const uint64_t slot0 = ((uint64_t)tile * nwaves + wave) * (uint64_t)(CH * kChunk) + lane * kLaneElems;
+
+    LaneSpan span[CH];
+    float v[CH][8];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        span[c] = lane_span(slot0 + (uint64_t)c * kChunk, p);
+        load_lane(x, p.center, span[c], v[c]);
+    }
+
+    float norm[CH];
+    if (PRE) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) norm[c] = span[c].bucket < p.nb ? norms[span[c].bucket] : 0.0f;
+    } else {
+        float t[CH];
+        const uint32_t lanes_per_bucket = (uint32_t)((N < kChunk ? N : kChunk) / kLaneElems);
+#pragma unroll
+        for (int c = 0; c < CH; ++c) t[c] = lane_butterfly<KIND>(lane_tree<KIND>(v[c]), lanes_per_bucket);
+        if (N > kChunk) {
+            const uint32_t chunks_per_bucket = (uint32_t)(N / kChunk < (uint64_t)CH ? N / kChunk : (uint64_t)CH);
+#pragma unroll
+            for (int w = 1; w < CH; w <<= 1) {
+                if (chunks_per_bucket > (uint32_t)w) {
+#pragma unroll
+                    for (int c = 0; c < CH; c += 2 * w) t[c] = combine<KIND>(t[c], t[c + w]);
+                }
+            }
+            if (N > (uint64_t)(CH * kChunk)) {          // the bucket spans several waves
+                const uint32_t waves_per_bucket = (uint32_t)(N / (CH * kChunk));
+                if (lane == 0) sm[wave] = t[0];
+                __syncthreads();
+                t[0] = lds_tree16<KIND>(sm, wave & ~(waves_per_bucket - 1u), waves_per_bucket);
+            }
+#pragma unroll
+            for (int w = CH / 2; w >= 1; w >>= 1) {
+                if (chunks_per_bucket > (uint32_t)w) {
+#pragma unroll
+                    for (int c = 0; c < CH; c += 2 * w) t[c + w] = t[c];
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            norm[c] = (KIND == QESGD_NORM_L2) ? sqrtf(t[c]) : t[c];
+            if (span[c].opens_bucket) norms[span[c].bucket] = norm[c];
+        }
+    }
+
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const uint64_t g = span[c].i >> 3;
+        uint32_t rnd[4];
+        philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), p.worker0 + k, p.round, p.key0, p.key1, rnd);
+        uint32_t sign_byte, bits[4];
+        round_and_pack<M>(v[c], rnd, inverse_step(norm[c], p.smax), p.smax, sign_byte, bits);
+        store_codes<M>(signs, levels, span[c].i, span[c].nvalid, lane, sign_byte, bits);
+    }
+}
+
+template <int M, int CH, int KIND, bool PRE>
+__global__ void k_quantize_pack(const QParams p) {
+    __shared__ float sm[32];
+    const uint32_t k = blockIdx.x / p.tiles_per_worker;
+    const uint32_t tile = p.tile0 + (blockIdx.x - k * p.tiles_per_worker);
+    guarded_tile<M, CH, KIND, PRE>(p, k, tile, sm);
 }
 
 // ---------------------------------------------------------------------------
@@ -343,7 +453,8 @@ __device__ __forceinline__ void process_tile(const FastCtx& cx, float (&v)[Geo<L
     }
 }
 
-// One tile per workgroup.  (Walking several tiles per workgroup with the next tile's loads
+// One tile per workgroup; the ragged last tile of a worker, if any, runs the guarded code in
+// the same launch.  (Walking several tiles per workgroup with the next tile's loads
 // in flight was measured and is slower: the packed stores of a long-lived workgroup spread
 // out in time and the mixed read/write stream to HBM loses more than the prefetch gains.)
 template <int M, int LOG2N, bool CENTER>
@@ -352,8 +463,13 @@ __global__ void __launch_bounds__(Geo<LOG2N>::NW * 64) k_quantize_pack_fast(cons
     constexpr uint32_t TILE = Geo<LOG2N>::TILE;
     __shared__ float sm[32];
 
-    const uint32_t k = blockIdx.x / p.full_tiles;
-    const uint32_t t = blockIdx.x - k * p.full_tiles;
+    const uint32_t per_worker = p.full_tiles + p.tail_tiles;
+    const uint32_t k = blockIdx.x / per_worker;
+    const uint32_t t = blockIdx.x - k * per_worker;
+    if (t >= p.full_tiles) {                              // the ragged last tile of the worker (at most one)
+        guarded_tile<M, CH, QESGD_NORM_L2, false>(p, k, t, sm);
+        return;
+    }
     const float* __restrict__ xk = p.x + (uint64_t)k * p.x_stride;
     const float* __restrict__ ck = p.center;
     unsigned char* __restrict__ out = p.packed + (uint64_t)k * p.packed_stride;
@@ -420,136 +536,6 @@ __global__ void __launch_bounds__(256) k_quantize_pack_pre_fast(const QParams p)
         uint32_t sign_byte, bits[4];
         round_and_pack<M>(v[c], rnd, inv, p.smax, sign_byte, bits);
         store_codes<M>(signs, levels, i, 8u, lane, sign_byte, bits);
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Generic kernel.
-// ---------------------------------------------------------------------------
-// Where the 8 slots of this lane fall: bucket, first coordinate, how many of
-// them are real coordinates (0..8), and whether they open the bucket.
-struct LaneSpan {
-    uint64_t bucket;
-    uint64_t i;        // first coordinate (a multiple of 8)
-    uint32_t nvalid;
-    bool opens_bucket;
-};
-
-__device__ __forceinline__ LaneSpan lane_span(uint64_t slot, const QParams& p) {
-    LaneSpan s;
-    const uint64_t N = 1ull << p.log2N;
-    s.bucket = slot >> p.log2N;
-    const uint64_t j = slot & (N - 1);
-    uint64_t len = 0;
-    if (s.bucket < p.nb) {
-        const uint64_t rem = p.d - s.bucket * p.B;
-        len = rem < p.B ? rem : p.B;
-    }
-    s.nvalid = j < len ? (uint32_t)((len - j) < 8 ? (len - j) : 8) : 0u;
-    s.i = s.bucket * p.B + j;
-    s.opens_bucket = (j == 0) && (s.bucket < p.nb);
-    return s;
-}
-
-__device__ __forceinline__ void load_lane(const float* __restrict__ x, const float* __restrict__ center,
-                                          const LaneSpan& s, float (&v)[8]) {
-    if (s.nvalid == 8) {
-        const float4 a = *reinterpret_cast<const float4*>(x + s.i);
-        const float4 b = *reinterpret_cast<const float4*>(x + s.i + 4);
-        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-        if (center) {
-            const float4 ca = *reinterpret_cast<const float4*>(center + s.i);
-            const float4 cb = *reinterpret_cast<const float4*>(center + s.i + 4);
-            v[0] -= ca.x; v[1] -= ca.y; v[2] -= ca.z; v[3] -= ca.w;
-            v[4] -= cb.x; v[5] -= cb.y; v[6] -= cb.z; v[7] -= cb.w;
-        }
-    } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float t = 0.0f;
-            if ((uint32_t)e < s.nvalid) {
-                t = x[s.i + e];
-                if (center) t -= center[s.i + e];
-            }
-            v[e] = t;
-        }
-    }
-}
-
-// PRE = true: the scales were computed by the partial-sum passes below and are
-// read from the norms plane.
-template <int M, int CH, int KIND, bool PRE>
-__global__ void k_quantize_pack(const QParams p) {
-    __shared__ float sm[32];
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wave = threadIdx.x >> 6;
-    const uint32_t nwaves = blockDim.x >> 6;
-    const uint32_t k = blockIdx.x / p.tiles_per_worker;
-    const uint32_t tile = p.tile0 + (blockIdx.x - k * p.tiles_per_worker);
-    const float* __restrict__ x = p.x + (uint64_t)k * p.x_stride;
-    unsigned char* __restrict__ out = p.packed + (uint64_t)k * p.packed_stride;
-    float* __restrict__ norms = reinterpret_cast<float*>(out + p.norms_off);
-    uint32_t* __restrict__ signs = reinterpret_cast<uint32_t*>(out + p.signs_off);
-    uint32_t* __restrict__ levels = reinterpret_cast<uint32_t*>(out + p.levels_off);
-    const uint64_t N = 1ull << p.log2N;
-    const uint64_t slot0 = ((uint64_t)tile * nwaves + wave) * (uint64_t)(CH * kChunk) + lane * kLaneElems;
-
-    LaneSpan span[CH];
-    float v[CH][8];
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        span[c] = lane_span(slot0 + (uint64_t)c * kChunk, p);
-        load_lane(x, p.center, span[c], v[c]);
-    }
-
-    float norm[CH];
-    if (PRE) {
-#pragma unroll
-        for (int c = 0; c < CH; ++c) norm[c] = span[c].bucket < p.nb ? norms[span[c].bucket] : 0.0f;
-    } else {
-        float t[CH];
-        const uint32_t lanes_per_bucket = (uint32_t)((N < kChunk ? N : kChunk) / kLaneElems);
-#pragma unroll
-        for (int c = 0; c < CH; ++c) t[c] = lane_butterfly<KIND>(lane_tree<KIND>(v[c]), lanes_per_bucket);
-        if (N > kChunk) {
-            const uint32_t chunks_per_bucket = (uint32_t)(N / kChunk < (uint64_t)CH ? N / kChunk : (uint64_t)CH);
-#pragma unroll
-            for (int w = 1; w < CH; w <<= 1) {
-                if (chunks_per_bucket > (uint32_t)w) {
-#pragma unroll
-                    for (int c = 0; c < CH; c += 2 * w) t[c] = combine<KIND>(t[c], t[c + w]);
-                }
-            }
-            if (N > (uint64_t)(CH * kChunk)) {          // the bucket spans several waves
-                const uint32_t waves_per_bucket = (uint32_t)(N / (CH * kChunk));
-                if (lane == 0) sm[wave] = t[0];
-                __syncthreads();
-                t[0] = lds_tree16<KIND>(sm, wave & ~(waves_per_bucket - 1u), waves_per_bucket);
-            }
-#pragma unroll
-            for (int w = CH / 2; w >= 1; w >>= 1) {
-                if (chunks_per_bucket > (uint32_t)w) {
-#pragma unroll
-                    for (int c = 0; c < CH; c += 2 * w) t[c + w] = t[c];
-                }
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < CH; ++c) {
-            norm[c] = (KIND == QESGD_NORM_L2) ? sqrtf(t[c]) : t[c];
-            if (span[c].opens_bucket) norms[span[c].bucket] = norm[c];
-        }
-    }
-
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        const uint64_t g = span[c].i >> 3;
-        uint32_t rnd[4];
-        philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), p.worker0 + k, p.round, p.key0, p.key1, rnd);
-        uint32_t sign_byte, bits[4];
-        round_and_pack<M>(v[c], rnd, inverse_step(norm[c], p.smax), p.smax, sign_byte, bits);
-        store_codes<M>(signs, levels, span[c].i, span[c].nvalid, lane, sign_byte, bits);
     }
 }
 
@@ -775,17 +761,15 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
     if (a.norm_kind == QESGD_NORM_L2 && sh.N == sh.B && sh.log2N >= 5) full_tiles = sh.d / tile;
     if (full_tiles > 0) {
         p.full_tiles = (uint32_t)full_tiles;
-        launch_fast(p, sh.m, (uint32_t)(full_tiles * a.K), a.stream);
-        const int rc = check_launch();
-        if (rc != QESGD_OK) return rc;
+        p.tail_tiles = (uint32_t)(tiles - full_tiles);
+        launch_fast(p, sh.m, (uint32_t)(tiles * a.K), a.stream);
+        return check_launch();
     }
-    if (tiles > full_tiles) {
-        p.tile0 = (uint32_t)full_tiles;
-        p.tiles_per_worker = (uint32_t)(tiles - full_tiles);
-        const dim3 grid((uint32_t)((tiles - full_tiles) * a.K));
-        if (ch == 2) launch_m<2, false>(p, sh.m, a.norm_kind, grid, block, a.stream);
-        else launch_m<4, false>(p, sh.m, a.norm_kind, grid, block, a.stream);
-    }
+    p.tile0 = 0;
+    p.tiles_per_worker = (uint32_t)tiles;
+    const dim3 grid((uint32_t)(tiles * a.K));
+    if (ch == 2) launch_m<2, false>(p, sh.m, a.norm_kind, grid, block, a.stream);
+    else launch_m<4, false>(p, sh.m, a.norm_kind, grid, block, a.stream);
     return check_launch();
 }
 
