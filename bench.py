@@ -155,6 +155,8 @@ def main():
     ap.add_argument("--path", default="qesgd", choices=["qesgd", "fixed"],
                     help="qesgd: bucketed quantize-pack + unpack-aggregate-update (the headline path); "
                          "fixed: the paper-literal fixed-grid quantiser (b = 8) + its fused inverse")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a HIP graph (adds graph_replay_ms_per_step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (reference point for --pmc byte counters)")
@@ -256,6 +258,30 @@ def main():
         "roofline": roofline(dom),
         "roofline_other": roofline("unpack_aggregate_update" if dom == "quantize_pack" else "quantize_pack"),
     }
+    if args.graph:
+        # The same step replayed from a HIP graph (launch-bound shapes: cfg1, cfg2).  The round
+        # argument is frozen at capture, so every replay draws the same variates.
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            B.qesgd_quantize_pack_batched(slab, slab.stride(0), None, cfg.d, cfg.s, cfg.bucket, B.NORM_L2,
+                                          cfg.seed, 0, cfg.K, packed, packed.stride(0), ws)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            B.qesgd_quantize_pack_batched(slab, slab.stride(0), None, cfg.d, cfg.s, cfg.bucket, B.NORM_L2,
+                                          cfg.seed, 0, cfg.K, packed, packed.stride(0), ws)
+            B.qesgd_unpack_aggregate_update(packed, packed.stride(0), cfg.K, cfg.d, cfg.s, cfg.bucket, w, zbar, u,
+                                            zsum)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        out["graph_replay_ms_per_step"] = round((time.perf_counter() - g0) * 1e3 / args.steps, 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, slab, w, lay)
     print(json.dumps(out), flush=True)
