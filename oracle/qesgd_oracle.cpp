@@ -101,11 +101,34 @@ int level_bits_of(uint32_t s) {          // m = log2(s) for the supported s
     switch (s) {
         case 2: return 1;
         case 4: return 2;
+        case 8: return 3;
         case 16: return 4;
+        case 32: return 5;
+        case 64: return 6;
+        case 128: return 7;
         case 256: return 8;
         case 65536: return 16;
         default: return -1;
     }
+}
+
+// The level plane is one little-endian bit string: coordinate i owns bits
+// [i*m, i*m+m), bit t of the string being bit (t mod 32) of word t/32.  A field
+// whose width does not divide 32 may continue into the next word.
+void put_level(uint32_t* words, uint64_t i, uint64_t m, uint32_t level) {
+    for (uint64_t j = 0; j < m; ++j) {
+        const uint64_t t = i * m + j;
+        if ((level >> j) & 1u) words[t >> 5] |= 1u << (t & 31);
+    }
+}
+
+uint32_t get_level(const uint32_t* words, uint64_t i, uint64_t m) {
+    uint32_t level = 0;
+    for (uint64_t j = 0; j < m; ++j) {
+        const uint64_t t = i * m + j;
+        level |= ((words[t >> 5] >> (t & 31)) & 1u) << j;
+    }
+    return level;
 }
 
 uint64_t effective_bucket(uint64_t d, uint64_t bucket) { return bucket < d ? bucket : d; }
@@ -226,9 +249,8 @@ void qo_quantize_bucket(const float* v, uint64_t len, uint64_t padded_n, uint64_
 }
 
 // Codes -> words.  Coordinate i puts its sign in bit (i mod 32) of sign word
-// i/32 and its level in the m bits starting at bit (i*m mod 32) of level word
-// (i*m)/32; m divides 32, so no field straddles a word.  Unused high bits of the
-// last word of a plane are 0.
+// i/32 and its level in the m bits starting at bit i*m of the level plane's bit
+// string.  Unused high bits of the last word of a plane are 0.
 void qo_pack(const uint32_t* level, const uint8_t* sign, uint64_t d, uint32_t s,
              uint32_t* sign_words, uint32_t* level_words) {
     const uint64_t m = (uint64_t)level_bits_of(s);
@@ -237,19 +259,16 @@ void qo_pack(const uint32_t* level, const uint8_t* sign, uint64_t d, uint32_t s,
     for (uint64_t w = 0; w < nlw; ++w) level_words[w] = 0;
     for (uint64_t i = 0; i < d; ++i) {
         sign_words[i >> 5] |= (uint32_t)(sign[i] & 1u) << (i & 31);
-        const uint64_t bit = i * m;
-        level_words[bit >> 5] |= level[i] << (bit & 31);
+        put_level(level_words, i, m, level[i]);
     }
 }
 
 void qo_unpack(const uint32_t* sign_words, const uint32_t* level_words, uint64_t d, uint32_t s,
                uint32_t* level, uint8_t* sign) {
     const uint64_t m = (uint64_t)level_bits_of(s);
-    const uint32_t mask = (m == 32) ? 0xFFFFFFFFu : ((1u << m) - 1u);
     for (uint64_t i = 0; i < d; ++i) {
         sign[i] = (uint8_t)((sign_words[i >> 5] >> (i & 31)) & 1u);
-        const uint64_t bit = i * m;
-        level[i] = (level_words[bit >> 5] >> (bit & 31)) & mask;
+        level[i] = get_level(level_words, i, m);
     }
 }
 
@@ -293,15 +312,13 @@ int qo_unpack_aggregate_range(const float* norms, const uint32_t* sign_words,
     if (qo_shape(d, s, bucket, &nb, &nsw, &nlw, &N) != 0 || K == 0 || i_end > d) return -1;
     const uint64_t B = effective_bucket(d, bucket);
     const uint64_t m = (uint64_t)level_bits_of(s);
-    const uint32_t mask = (1u << m) - 1u;
     const float smax = (float)(s - 1);
     for (uint64_t i = i_begin; i < i_end; ++i) {
         const uint64_t b = i / B;
         float acc = 0.0f;
         for (uint32_t k = 0; k < K; ++k) {
             const float step = norms[(uint64_t)k * nb + b] / smax;
-            const uint64_t bit = i * m;
-            const uint32_t level = (level_words[(uint64_t)k * nlw + (bit >> 5)] >> (bit & 31)) & mask;
+            const uint32_t level = get_level(level_words + (uint64_t)k * nlw, i, m);
             const uint32_t sign = (sign_words[(uint64_t)k * nsw + (i >> 5)] >> (i & 31)) & 1u;
             float q = (float)level * step;
             if (sign) q = -q;

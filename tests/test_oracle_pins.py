@@ -13,8 +13,8 @@ import numpy as np
 import pytest
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
-LEVELS = [2, 4, 16, 256, 65536]
-MBITS = {2: 1, 4: 2, 16: 4, 256: 8, 65536: 16}
+LEVELS = [2, 4, 8, 16, 32, 64, 128, 256, 65536]
+MBITS = {2: 1, 4: 2, 8: 3, 16: 4, 32: 5, 64: 6, 128: 7, 256: 8, 65536: 16}
 
 
 def f32(x):
@@ -377,6 +377,36 @@ def test_pack_hand_example(oracle):
     # m = 1: the level plane is a bit mask
     sw, lw = oracle.pack(np.array([1, 0, 1, 1], np.uint32), np.array([0, 1, 0, 0], np.uint8), 2)
     assert list(lw) == [0b1101] and list(sw) == [0b0010]
+    # m = 3: coordinate 10 owns bits 30..32 and continues into the second word
+    level = np.array([1, 2, 3, 4, 5, 6, 7, 0, 1, 2, 0b101, 0b110], np.uint32)
+    sw, lw = oracle.pack(level, np.zeros(12, np.uint8), 8)
+    #            c9  c8  c7  c6  c5  c4  c3  c2  c1  c0, low two bits of c10 = 01 on top
+    assert list(lw) == [0b01_010_001_000_111_110_101_100_011_010_001, 0b110_1]
+    # m = 7: coordinate 4 owns bits 28..34
+    sw, lw = oracle.pack(np.array([0x7F, 0, 0x7F, 0, 0b1010011], np.uint32), np.zeros(5, np.uint8), 128)
+    assert list(lw) == [(0x7F) | (0x7F << 14) | (0b0011 << 28), 0b101]
+
+
+@pytest.mark.parametrize("s", LEVELS)
+def test_level_plane_is_one_little_endian_bit_string(oracle, s):
+    """The level plane read as one little-endian integer holds coordinate i in bits
+    [i*m, i*m+m): pins the layout for the widths that do not divide 32, where a field
+    continues into the next word (a field cut at the word boundary, or continued at
+    the wrong end of the next word, fails here)."""
+    rng = np.random.default_rng(100 + s)
+    m = MBITS[s]
+    for d in (1, 5, 31, 32, 33, 64, 100, 1021):
+        level = rng.integers(0, s, size=d).astype(np.uint32)
+        sign = rng.integers(0, 2, size=d).astype(np.uint8)
+        sw, lw = oracle.pack(level, sign, s)
+        X = int.from_bytes(lw.astype("<u4").tobytes(), "little")
+        assert [(X >> (i * m)) & (s - 1) for i in range(d)] == level.tolist()
+        assert X >> (d * m) == 0
+        # and the reader inverts an integer built the same way
+        Y = sum(int(l) << (i * m) for i, l in enumerate(level))
+        words = np.frombuffer(Y.to_bytes(lw.size * 4, "little"), dtype="<u4").astype(np.uint32)
+        l2, _ = oracle.unpack(sw, words, d, s)
+        assert np.array_equal(l2, level)
 
 
 @pytest.mark.parametrize("s", LEVELS)
@@ -432,7 +462,8 @@ def _random_packed(rng, K, d, s, B):
     return norms, sw, lw
 
 
-@pytest.mark.parametrize("s,K", [(2, 8), (4, 3), (16, 8), (256, 16), (65536, 5)])
+@pytest.mark.parametrize("s,K", [(2, 8), (4, 3), (8, 5), (16, 8), (32, 2), (64, 7), (128, 4),
+                                 (256, 16), (65536, 5)])
 def test_aggregate_against_double(oracle, s, K):
     rng = np.random.default_rng(s + K)
     d, B = 777, 96
