@@ -23,8 +23,9 @@
  *     subnormals kept; results do not depend on the launch geometry.
  *
  * Quantiser (one reading of what the paper leaves open)
- *   - s magnitude levels {0..s-1}, s in {2,4,16,256,65536}; m = log2(s) level
- *     bits plus one sign bit per coordinate; grid step delta_b = norm_b/(s-1).
+ *   - s magnitude levels {0..s-1}, s in {2,4,8,16,32,64,128,256,65536}; m =
+ *     log2(s) level bits plus one sign bit per coordinate; grid step delta_b =
+ *     norm_b/(s-1).  (The widths that divide 32 take the specialised kernels.)
  *   - bucket b covers coordinates [b*bucket, min((b+1)*bucket, d)); bucket >= d
  *     means a single bucket; otherwise bucket must be a multiple of 32.
  *   - norm_b: L2 norm (fp32 sum of squares added as a balanced binary tree over
@@ -40,7 +41,10 @@
  * multiple of 256):
  *     float    norms [n_buckets]              at norms_off
  *     uint32_t signs [ceil(d/32)]             at signs_off   bit (i&31) of word i>>5
- *     uint32_t levels[ceil(d*m/32)]           at levels_off  m bits at bit (i*m)&31 of word (i*m)>>5
+ *     uint32_t levels[ceil(d*m/32)]           at levels_off  bits [i*m, i*m+m) of the plane read as
+ *                                                            one little-endian bit string (bit t = bit
+ *                                                            t&31 of word t>>5; for m = 3,5,6,7 a
+ *                                                            field may continue in the next word)
  *   Unused high bits of the last word of a plane are written as 0; bytes
  *   between the planes are never written.
  */
@@ -61,7 +65,7 @@ enum {
     QESGD_OK = 0,
     QESGD_ERR_NULL = -1,       /* a required pointer is NULL                          */
     QESGD_ERR_DIM = -2,        /* d == 0 or d >= 2^40                                 */
-    QESGD_ERR_LEVELS = -3,     /* s not in {2,4,16,256,65536}                          */
+    QESGD_ERR_LEVELS = -3,     /* s not 2,4,8,16,32,64,128,256 or 65536                */
     QESGD_ERR_BUCKET = -4,     /* bucket == 0, or bucket < d and bucket % 32 != 0      */
     QESGD_ERR_WORKERS = -5,    /* K == 0 or K > QESGD_MAX_WORKERS                      */
     QESGD_ERR_NORM_KIND = -6,  /* norm_kind not QESGD_NORM_L2 / QESGD_NORM_MAX         */

@@ -51,13 +51,28 @@ __device__ __forceinline__ void load8(const float* __restrict__ src, uint64_t i,
     }
 }
 
-// The 8*M level bits of the lane's coordinates, as up to four words.
+// The 8*M level bits of the lane's coordinates, as up to four words.  For a
+// width that does not divide 32 the lane's M bytes start at byte (i/8)*M of the
+// plane, at any alignment: the two or three words that hold them are read and
+// shifted down so that coordinate i's field starts at bit 0 of w[0].
 template <int M>
 __device__ __forceinline__ void load_level_bits(const uint32_t* __restrict__ levels, uint64_t i, uint32_t nvalid,
                                                 uint64_t level_words, uint32_t (&w)[4]) {
     w[0] = w[1] = w[2] = w[3] = 0;
     const unsigned char* bytes = reinterpret_cast<const unsigned char*>(levels);
-    if (M == 1) {
+    if (M == 3 || M == 5 || M == 6 || M == 7) {
+        const uint64_t byte0 = (i >> 3) * (uint64_t)M;
+        const uint64_t a = byte0 >> 2;
+        const uint32_t sh = 8u * (uint32_t)(byte0 & 3u);
+        const uint32_t t0 = a < level_words ? levels[a] : 0u;
+        const uint32_t t1 = a + 1 < level_words ? levels[a + 1] : 0u;
+        const uint32_t t2 = (M == 7 && a + 2 < level_words) ? levels[a + 2] : 0u;   // 7 bytes from byte 2 or 3 reach a third word
+        const uint64_t lo = (uint64_t)t0 | ((uint64_t)t1 << 32);
+        uint64_t v = lo >> sh;
+        if (M == 7 && sh != 0u) v |= (uint64_t)t2 << (64u - sh);
+        w[0] = (uint32_t)v;
+        w[1] = (uint32_t)(v >> 32);
+    } else if (M == 1) {
         w[0] = bytes[i >> 3];
     } else if (M == 2) {
         w[0] = *reinterpret_cast<const unsigned short*>(bytes + (i >> 2));
@@ -87,6 +102,10 @@ template <int M>
 __device__ __forceinline__ uint32_t level_of(const uint32_t (&w)[4], int e) {
     constexpr uint32_t mask = (1u << M) - 1u;
     const int bit = e * M;
+    if ((bit & 31) + M > 32) {                            // the field continues in the next word
+        const uint64_t both = (uint64_t)w[bit >> 5] | ((uint64_t)w[(bit >> 5) + 1] << 32);
+        return (uint32_t)(both >> (bit & 31)) & mask;
+    }
     return (w[bit >> 5] >> (bit & 31)) & mask;
 }
 
@@ -341,7 +360,11 @@ int launch_aggregate(const Shape& sh, const AggregateArgs& a) {
     switch (sh.m) {
         case 1: QESGD_LAUNCH_AGG(1); break;
         case 2: QESGD_LAUNCH_AGG(2); break;
+        case 3: QESGD_LAUNCH_AGG(3); break;
         case 4: QESGD_LAUNCH_AGG(4); break;
+        case 5: QESGD_LAUNCH_AGG(5); break;
+        case 6: QESGD_LAUNCH_AGG(6); break;
+        case 7: QESGD_LAUNCH_AGG(7); break;
         case 8: QESGD_LAUNCH_AGG(8); break;
         default: QESGD_LAUNCH_AGG(16); break;
     }

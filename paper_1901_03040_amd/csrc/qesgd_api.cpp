@@ -11,7 +11,11 @@ static int level_bits(uint32_t s) {
     switch (s) {
         case 2u: return 1;
         case 4u: return 2;
+        case 8u: return 3;
         case 16u: return 4;
+        case 32u: return 5;
+        case 64u: return 6;
+        case 128u: return 7;
         case 256u: return 8;
         case 65536u: return 16;
         default: return -1;
@@ -217,7 +221,7 @@ const char* qesgd_strerror(int code) {
         case QESGD_OK: return "ok";
         case QESGD_ERR_NULL: return "a required pointer is NULL";
         case QESGD_ERR_DIM: return "d must be in [1, 2^40)";
-        case QESGD_ERR_LEVELS: return "s must be one of 2, 4, 16, 256, 65536";
+        case QESGD_ERR_LEVELS: return "s must be one of 2, 4, 8, 16, 32, 64, 128, 256, 65536";
         case QESGD_ERR_BUCKET: return "bucket must be > 0 and, when smaller than d, a multiple of 32";
         case QESGD_ERR_WORKERS: return "K must be in [1, 64]";
         case QESGD_ERR_NORM_KIND: return "norm_kind must be 0 (L2) or 1 (max)";

@@ -63,6 +63,7 @@ __device__ __forceinline__ float dpp_f32(float x) {
 }
 constexpr int kDppXor1 = 0xB1;          // quad_perm [1,0,3,2]
 constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int kDppQuadLane0 = 0x00;     // quad_perm [0,0,0,0]: lane 0 of the quad to all four
 constexpr int kDppHalfMirror = 0x141;   // lane l -> 7 - l inside each 8: the other quad
 constexpr int kDppRowMirror = 0x140;    // lane l -> 15 - l inside each 16: the other 8
 
@@ -167,6 +168,12 @@ __device__ __forceinline__ void round_and_pack(const float (&v)[8], const uint32
 #pragma unroll
         for (int e = 1; e < 8; ++e) w |= (y[e] >> 16) << (M * e);
         bits[0] = w;
+    } else if (M == 3 || M == 5 || M == 6 || M == 7) {       // 8*M <= 56 bits: one 64-bit string
+        uint64_t w = y[0] >> 16;
+#pragma unroll
+        for (int e = 1; e < 8; ++e) w |= (uint64_t)(y[e] >> 16) << (M * e);
+        bits[0] = (uint32_t)w;
+        bits[1] = (uint32_t)(w >> 32);
     } else if (M == 8) {
         bits[0] = (y[0] >> 16) | ((y[1] >> 16) << 8) | ((y[2] >> 16) << 16) | ((y[3] >> 16) << 24);
         bits[1] = (y[4] >> 16) | ((y[5] >> 16) << 8) | ((y[6] >> 16) << 16) | ((y[7] >> 16) << 24);
@@ -208,6 +215,35 @@ __device__ __forceinline__ void store_codes(uint32_t* __restrict__ sign_words, u
         if ((lane & 1u) == 0u && nvalid > 0) level_words[i >> 4] = w;
     } else if (M == 4) {
         if (nvalid > 0) level_words[i >> 3] = bits[0];
+    } else if (M == 3 || M == 5 || M == 6 || M == 7) {
+        // The 32 coordinates of a quad fill M whole words; lane j's 8*M bits start at bit
+        // 8*M*j of that block.  Every lane shifts its string into each of the M words, the
+        // quad ORs them, and lane j stores words j and j+4 of the block (those that hold a
+        // coordinate of the vector).
+        const uint32_t j = lane & 3u;
+        uint32_t nq = nvalid;
+        nq += dpp_u32<kDppXor1>(nq);
+        nq += dpp_u32<kDppXor2>(nq);
+        const uint32_t nwords = (nq * (uint32_t)M + 31u) >> 5;
+        const uint64_t i_quad = (uint64_t)dpp_u32<kDppQuadLane0>((uint32_t)i) |
+                                ((uint64_t)dpp_u32<kDppQuadLane0>((uint32_t)(i >> 32)) << 32);
+        const uint64_t v = (uint64_t)bits[0] | ((uint64_t)bits[1] << 32);
+        const int at = 8 * M * (int)j;
+        uint32_t first = 0, second = 0;
+#pragma unroll
+        for (int q = 0; q < M; ++q) {
+            const int sh = at - 32 * q;                   // where the string starts relative to word q
+            uint32_t c = 0;
+            if (sh >= 0 && sh < 32) c = (uint32_t)v << sh;
+            else if (sh < 0 && sh > -64) c = (uint32_t)(v >> (-sh));
+            c |= dpp_u32<kDppXor1>(c);
+            c |= dpp_u32<kDppXor2>(c);
+            if (q < 4) { if (j == (uint32_t)q) first = c; }
+            else { if (j == (uint32_t)(q - 4)) second = c; }
+        }
+        uint32_t* __restrict__ dst = level_words + (i_quad >> 5) * (uint64_t)M;
+        if (j < nwords) dst[j] = first;
+        if (M > 4 && j + 4u < nwords) dst[j + 4u] = second;
     } else if (M == 8) {
         if (nvalid == 8) {
             *reinterpret_cast<uint2*>(level_words + (i >> 2)) = make_uint2(bits[0], bits[1]);
@@ -616,7 +652,11 @@ void launch_m(const QParams& p, uint32_t m, uint32_t norm_kind, dim3 grid, dim3 
     switch (m) {
         case 1: launch_kind<1, CH, PRE>(p, norm_kind, grid, block, st); break;
         case 2: launch_kind<2, CH, PRE>(p, norm_kind, grid, block, st); break;
+        case 3: launch_kind<3, CH, PRE>(p, norm_kind, grid, block, st); break;
         case 4: launch_kind<4, CH, PRE>(p, norm_kind, grid, block, st); break;
+        case 5: launch_kind<5, CH, PRE>(p, norm_kind, grid, block, st); break;
+        case 6: launch_kind<6, CH, PRE>(p, norm_kind, grid, block, st); break;
+        case 7: launch_kind<7, CH, PRE>(p, norm_kind, grid, block, st); break;
         case 8: launch_kind<8, CH, PRE>(p, norm_kind, grid, block, st); break;
         default: launch_kind<16, CH, PRE>(p, norm_kind, grid, block, st); break;
     }
@@ -667,7 +707,11 @@ void launch_pre_fast(const QParams& p, uint32_t m, uint32_t blocks, hipStream_t 
     switch (m) {
         case 1: launch_pre_fast_m<1>(p, blocks, st); break;
         case 2: launch_pre_fast_m<2>(p, blocks, st); break;
+        case 3: launch_pre_fast_m<3>(p, blocks, st); break;
         case 4: launch_pre_fast_m<4>(p, blocks, st); break;
+        case 5: launch_pre_fast_m<5>(p, blocks, st); break;
+        case 6: launch_pre_fast_m<6>(p, blocks, st); break;
+        case 7: launch_pre_fast_m<7>(p, blocks, st); break;
         case 8: launch_pre_fast_m<8>(p, blocks, st); break;
         default: launch_pre_fast_m<16>(p, blocks, st); break;
     }
@@ -756,9 +800,10 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
     }
 
     // Tiles that lie wholly inside the vector go to the fast kernel when the bucket is a
-    // power of two (slot == coordinate) and the scale is the L2 norm.
+    // power of two (slot == coordinate), the scale is the L2 norm and the level width
+    // divides a word (the other widths are served by the generic kernel alone).
     uint64_t full_tiles = 0;
-    if (a.norm_kind == QESGD_NORM_L2 && sh.N == sh.B && sh.log2N >= 5) full_tiles = sh.d / tile;
+    if (a.norm_kind == QESGD_NORM_L2 && sh.N == sh.B && sh.log2N >= 5 && 32u % sh.m == 0u) full_tiles = sh.d / tile;
     if (full_tiles > 0) {
         p.full_tiles = (uint32_t)full_tiles;
         p.tail_tiles = (uint32_t)(tiles - full_tiles);

@@ -30,7 +30,7 @@ def test_exports_every_declared_symbol(B):
 
 
 def test_error_strings(B):
-    for code in range(0, -11, -1):
+    for code in range(0, -14, -1):
         assert B.strerror(code) and "unknown" not in B.strerror(code)
     assert "unknown" in B.strerror(-99)
 
@@ -38,7 +38,7 @@ def test_error_strings(B):
 @pytest.mark.parametrize("d,s,bucket,nb,m", [
     (16_384, 4, 16_384, 1, 2), (1_048_576, 16, 512, 2048, 4), (11_173_962, 4, 2048, 5457, 2),
     (25_557_032, 256, 8192, 3120, 8), (138_357_544, 2, 4096, 33_779, 1), (1000, 65536, 96, 11, 16),
-    (5, 2, 4096, 1, 1)])
+    (5, 2, 4096, 1, 1), (1001, 8, 96, 11, 3), (1001, 32, 96, 11, 5), (77, 64, 4096, 1, 6), (33, 128, 32, 2, 7)])
 def test_layout(B, d, s, bucket, nb, m):
     lay = B.qesgd_layout_query(d, s, bucket)
     assert (lay.n_buckets, lay.level_bits) == (nb, m)
