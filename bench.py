@@ -28,6 +28,20 @@ def algorithmic_bytes(cfg, lay):
     return q, uau
 
 
+def host_cpu():
+    """Model name and online CPU count of the host the oracle is timed on."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"model": model, "online_cpus": os.cpu_count()}
+
+
 def cpu_baseline(cfg, slab, w, lay, budget_elems=1 << 26):
     """The oracle as it stands, one host thread, on a bucket-aligned prefix of the same workload."""
     import numpy as np
@@ -56,7 +70,7 @@ def cpu_baseline(cfg, slab, w, lay, budget_elems=1 << 26):
                   f"({cfg.K * ds} coordinate quantisations)",
         "quantize_GBps": round(qb / tq / 1e9, 4), "aggregate_update_GBps": round(ub / tu / 1e9, 4),
         "quantize_params_per_s": round(cfg.K * ds / tq), "aggregate_update_params_per_s": round(ds / tu),
-        "seconds": round(tq + tu, 2),
+        "seconds": round(tq + tu, 2), "host": host_cpu(),
     }
 
 
@@ -142,7 +156,7 @@ def bench_fixed_grid(args, cfg, torch, B, synth, dev):
                                "sample": f"first {ds} of {d} coordinates, one step",
                                "quantize_params_per_s": round(ds / (t1 - t0)),
                                "dequantize_update_params_per_s": round(ds / (t2 - t1)),
-                               "seconds": round(t2 - t0, 2)}
+                               "seconds": round(t2 - t0, 2), "host": host_cpu()}
     print(json.dumps(out), flush=True)
 
 

@@ -12,13 +12,19 @@
 // chunks of a wave, then the waves of a workgroup through LDS.  Every lane ends
 // with its bucket's total, so the scale never goes through memory.
 //
-// Two kernels share the arithmetic:
-//   k_quantize_pack_fast  power-of-two buckets, L2 scale, tiles that lie wholly
-//                         inside the vector.  N is a template parameter, so the
-//                         whole tile is straight-line code without guards.
-//   k_quantize_pack       everything else: ragged last tile, buckets that are
-//                         not a power of two, max-norm, tiny vectors, and the
-//                         second pass of buckets too wide for one workgroup.
+// The kernels share the arithmetic:
+//   k_quantize_pack_fast  power-of-two buckets, L2 scale, level width dividing
+//                         32, tiles that lie wholly inside the vector.  N is a
+//                         template parameter, so the whole tile is straight-line
+//                         code without guards; the ragged last tile of a worker
+//                         runs the guarded body in the same launch.
+//   k_quantize_pack       everything else: buckets that are not a power of two,
+//                         max-norm, level widths 3/5/6/7, tiny vectors, and the
+//                         last pass of buckets too wide for one workgroup.
+//   k_tile_partials(_fast), k_finish_norms, k_quantize_pack_pre_fast
+//                         buckets wider than kMaxSinglePassBucket: per-tile tree
+//                         sums into the workspace, the rest of each bucket's
+//                         tree, then the quantiser with the scale read back.
 #include "qesgd_device.h"
 #include "qesgd_internal.h"
 
@@ -137,7 +143,8 @@ __device__ __forceinline__ float lds_tree16(const float* sm, uint32_t base, uint
 // inv * 2^16 is folded into the scale when it is finite: scaling by a power of
 // two commutes with rounding, and a product that underflows truncates to 0
 // either way.  bits[] receives the 8*M level bits (M = 1: low byte, M = 2: low
-// half, M = 4: one word, M = 8: two words, M = 16: four words).
+// half, M = 4: one word, M = 8: two words, M = 16: four words; M = 3, 5, 6, 7:
+// the low 8*M bits of bits[0..1] read as one 64-bit string).
 // ---------------------------------------------------------------------------
 template <int M>
 __device__ __forceinline__ void round_and_pack(const float (&v)[8], const uint32_t (&rnd)[4], float inv,
