@@ -160,6 +160,45 @@ def bench_fixed_grid(args, cfg, torch, B, synth, dev):
     print(json.dumps(out), flush=True)
 
 
+def bench_ceilings(args, cfg, torch, B, synth, dev):
+    """Plain streaming kernels with the two hot kernels' access mixes, on the workload's footprint:
+    what this machine reaches with no arithmetic.  Prints one JSON line of its own."""
+    stride = synth.slab_stride(cfg.d)
+    n_slab = cfg.K * stride // 4096 * 4096            # floats the quantiser reads per round
+    n_vec = cfg.d // 4096 * 4096                      # floats per parameter-sized vector
+    slab = synth.worker_slab(cfg, dev).view(-1)
+    planes = [torch.empty(n_slab // 32, dtype=torch.float32, device=dev) for _ in range(2)]
+    vec = [torch.empty(n_vec, dtype=torch.float32, device=dev).normal_() for _ in range(5)]
+    stream = torch.cuda.current_stream()
+    n_copy = n_slab
+    dst = torch.empty(n_copy, dtype=torch.float32, device=dev)
+    cases = [
+        ("read_only", B.PROBE_READ, (slab, dst, None, None, None), n_slab, 4 * n_slab),
+        ("copy", B.PROBE_COPY, (slab, dst, None, None, None), n_copy, 8 * n_copy),
+        ("quantize_mix_read_plus_2_packed_planes", B.PROBE_QUANTIZE_MIX, (slab, planes[0], planes[1], None, None),
+         n_slab, 4 * n_slab + 2 * (n_slab // 8)),
+        ("update_mix_2_reads_3_writes", B.PROBE_UPDATE_MIX, tuple(vec), n_vec, 20 * n_vec),
+    ]
+    out = {"ceilings": {}, "unit": "GB/s", "config": {"workload": f"{cfg.name} footprint: d={cfg.d}, K={cfg.K}"}, "steps": args.steps,
+           "warmup": args.warmup, "hbm_peak": HBM_PEAK_GBPS}
+    for name, pattern, bufs, n, nbytes in cases:
+        ms = []
+        for r in range(args.warmup + args.steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            B.qesgd_stream_probe(pattern, *bufs, n, stream)
+            e1.record(stream)
+            e1.synchronize()
+            if r >= args.warmup:
+                ms.append(e0.elapsed_time(e1))
+        ms.sort()
+        med = ms[len(ms) // 2]
+        out["ceilings"][name] = {"bytes": nbytes, "ms_median": round(med, 4), "ms_min": round(ms[0], 4),
+                                 "GBps": round(nbytes / med / 1e6, 1),
+                                 "frac_of_hbm_peak": round(nbytes / med / 1e6 / HBM_PEAK_GBPS, 4)}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -171,6 +210,9 @@ def main():
                          "fixed: the paper-literal fixed-grid quantiser (b = 8) + its fused inverse")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a HIP graph (adds graph_replay_ms_per_step)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of the benchmark, time plain streaming kernels with the hot kernels' "
+                         "access mixes on the workload's footprint (practical HBM ceilings of this machine)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (reference point for --pmc byte counters)")
@@ -190,6 +232,8 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     cfg = synth.by_name(args.config)
+    if args.ceilings:
+        return bench_ceilings(args, cfg, torch, B, synth, dev)
     if args.path == "fixed":
         return bench_fixed_grid(args, cfg, torch, B, synth, dev)
     lay = B.qesgd_layout_query(cfg.d, cfg.s, cfg.bucket)

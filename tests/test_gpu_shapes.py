@@ -64,3 +64,31 @@ def test_sixty_four_workers_with_center(oracle, B):
     slab[:, :d] = torch.randn(K, d, generator=g) * 1e-3
     c = torch.randn(d, generator=g) * 1e-3
     run_and_compare(oracle, B, slab.cuda(), 4, 1024, 3, 9, K=K, center=c.cuda(), d=d)
+
+
+def test_stream_probe_kernels_stay_in_their_buffers(B):
+    """The measurement-aid kernels: copy and update mix give the expected values, the quantiser
+    mix writes exactly n/32 words per plane, and nothing beyond the stated sizes is touched."""
+    n = 3 * 4096
+    g = torch.Generator(device="cuda").manual_seed(1)
+    a = torch.randn(n + 64, generator=g, device="cuda")
+    b = torch.randn(n + 64, generator=g, device="cuda")
+    guard = 123.0
+    c, d, e = (torch.full((n + 64,), guard, device="cuda") for _ in range(3))
+    B.qesgd_stream_probe(B.PROBE_UPDATE_MIX, a, b, c, d, e, n)
+    torch.cuda.synchronize()
+    assert torch.equal(c[:n], a[:n]) and torch.equal(e[:n], b[:n]) and torch.equal(d[:n], a[:n] + b[:n])
+    assert all(bool((t[n:] == guard).all()) for t in (c, d, e))
+    c.fill_(guard)
+    B.qesgd_stream_probe(B.PROBE_COPY, a, c, None, None, None, n)
+    torch.cuda.synchronize()
+    assert torch.equal(c[:n], a[:n]) and bool((c[n:] == guard).all())
+    p0 = torch.full((n // 32 + 16,), guard, device="cuda")
+    p1 = torch.full((n // 32 + 16,), guard, device="cuda")
+    B.qesgd_stream_probe(B.PROBE_QUANTIZE_MIX, a, p0, p1, None, None, n)
+    before = b.clone()
+    B.qesgd_stream_probe(B.PROBE_READ, a, b, None, None, None, n)
+    torch.cuda.synchronize()
+    assert bool((p0[n // 32:] == guard).all()) and bool((p1[n // 32:] == guard).all())
+    assert not bool((p0[:n // 32] == guard).any())
+    assert torch.equal(b, before)
