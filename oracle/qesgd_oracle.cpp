@@ -19,7 +19,10 @@
 //
 // What the paper leaves open and this file fixes (one reading each):
 //   * "s levels": magnitudes {0, ..., s-1}, grid step delta = norm / (s-1),
-//     one sign bit plus m = log2(s) magnitude bits per coordinate.
+//     one sign bit plus m = log2(s) magnitude bits per coordinate
+//     (s = 2, 4, 8, 16, 32, 64, 128, 256, 65536).
+//   * the packed form: a plane of sign bits and a plane of m-bit levels, each
+//     one little-endian bit string cut into 32-bit words.
 //   * the uniform variate has 16 bits: with a = |v| / delta, l = floor(a),
 //     f = a - l, T = trunc(f * 2^16), the value is rounded up iff
 //     r + T >= 2^16 for a 16-bit uniform r, so P(up) = T / 2^16 in (f - 2^-16, f].
