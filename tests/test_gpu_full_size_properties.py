@@ -75,3 +75,37 @@ def test_every_coordinate_of_a_worker(B, S, name):
         t = ((q - v)[live].double() / step[live].double())
         n = int(live.sum())
         assert abs(float(t.mean())) <= 4 * 0.5 / math.sqrt(n) + 2.0 ** -16, (float(t.mean()), n)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+def test_aggregate_every_coordinate_against_fp64(B, S, name):
+    """zbar at full size against the sum over workers recomputed in fp64 from planes decoded with
+    torch integer ops (Alg. 3, server task): |zbar - mean| <= (K+3) 2^-24 mean|q| for every
+    coordinate; u and zsum are then exact fp32 sums of their inputs."""
+    from test_gpu_parity import random_packed
+    cfg = S.by_name(name)
+    d, K, s, bucket = cfg.d, cfg.K, cfg.s, cfg.bucket
+    lay, packed = random_packed(B, S, d, s, bucket, K, seed=cfg.seed + 100)
+    m = lay.level_bits
+    Bk = min(bucket, d)
+    w = S.snapshot(cfg, "cuda")
+    zsum0 = torch.empty(d, device="cuda").normal_(0.0, 1e-3, generator=torch.Generator(device="cuda").manual_seed(3))
+    zsum = zsum0.clone()
+    zbar = torch.empty(d, device="cuda")
+    u = torch.empty(d, device="cuda")
+    B.qesgd_unpack_aggregate_update(packed, packed.stride(0), K, d, s, bucket, w, zbar, u, zsum)
+    torch.cuda.synchronize()
+    total = torch.zeros(d, dtype=torch.float64, device="cuda")
+    mag = torch.zeros(d, dtype=torch.float64, device="cuda")
+    for k in range(K):
+        norms, sg, lv = B.planes(packed[k], lay)
+        sign = decode_plane(sg, d, 1)
+        level = decode_plane(lv, d, m)
+        q = level.double() * (norms.double() / float(s - 1)).repeat_interleave(Bk)[:d]
+        mag += q
+        total += torch.where(sign == 1, -q, q)
+        del sign, level, q
+    want = total / K
+    bound = (K + 3) * 2.0 ** -24 * mag / K + 1e-45
+    assert bool(((zbar.double() - want).abs() <= bound).all())
+    assert torch.equal(u, w + zbar) and torch.equal(zsum, zsum0 + zbar)
