@@ -160,6 +160,28 @@ def bench_fixed_grid(args, cfg, torch, B, synth, dev):
     print(json.dumps(out), flush=True)
 
 
+PROBE_READ, PROBE_COPY, PROBE_QUANTIZE_MIX, PROBE_UPDATE_MIX, PROBE_BYTE_CODES_MIX = range(5)
+
+
+def load_probe():
+    """The plain streaming kernels of libqesgd_bench_probe.so (a benchmark aid built next to the
+    library, not part of its ABI).  Returns probe(pattern, a, b, c, d, e, n, torch_stream)."""
+    import ctypes as C
+    path = os.path.join(ROOT, "paper_1901_03040_amd", "libqesgd_bench_probe.so")
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} not found: build it with `python -m paper_1901_03040_amd.build`")
+    L = C.CDLL(path)
+    L.qesgd_bench_probe.argtypes = [C.c_uint32] + [C.c_void_p] * 5 + [C.c_uint64, C.c_void_p]
+    L.qesgd_bench_probe.restype = C.c_int
+
+    def probe(pattern, a, b, c, d, e, n, stream):
+        ptr = [None if t is None else C.c_void_p(t.data_ptr()) for t in (a, b, c, d, e)]
+        rc = L.qesgd_bench_probe(int(pattern), *ptr, int(n), C.c_void_p(stream.cuda_stream))
+        if rc != 0:
+            raise RuntimeError(f"qesgd_bench_probe({pattern}) failed with code {rc}")
+    return probe
+
+
 def bench_ceilings(args, cfg, torch, B, synth, dev):
     """Plain streaming kernels with the two hot kernels' access mixes, on the workload's footprint:
     what this machine reaches with no arithmetic.  Prints one JSON line of its own."""
@@ -172,12 +194,15 @@ def bench_ceilings(args, cfg, torch, B, synth, dev):
     stream = torch.cuda.current_stream()
     n_copy = n_slab
     dst = torch.empty(n_copy, dtype=torch.float32, device=dev)
+    probe = load_probe()
     cases = [
-        ("read_only", B.PROBE_READ, (slab, dst, None, None, None), n_slab, 4 * n_slab),
-        ("copy", B.PROBE_COPY, (slab, dst, None, None, None), n_copy, 8 * n_copy),
-        ("quantize_mix_read_plus_2_packed_planes", B.PROBE_QUANTIZE_MIX, (slab, planes[0], planes[1], None, None),
+        ("read_only", PROBE_READ, (slab, dst, None, None, None), n_slab, 4 * n_slab),
+        ("copy", PROBE_COPY, (slab, dst, None, None, None), n_copy, 8 * n_copy),
+        ("quantize_mix_read_plus_2_packed_planes", PROBE_QUANTIZE_MIX, (slab, planes[0], planes[1], None, None),
          n_slab, 4 * n_slab + 2 * (n_slab // 8)),
-        ("update_mix_2_reads_3_writes", B.PROBE_UPDATE_MIX, tuple(vec), n_vec, 20 * n_vec),
+        ("byte_codes_mix_read_plus_1_byte_per_float", PROBE_BYTE_CODES_MIX, (vec[0], vec[1], None, None, None),
+         n_vec, 5 * n_vec),
+        ("update_mix_2_reads_3_writes", PROBE_UPDATE_MIX, tuple(vec), n_vec, 20 * n_vec),
     ]
     out = {"ceilings": {}, "unit": "GB/s", "config": {"workload": f"{cfg.name} footprint: d={cfg.d}, K={cfg.K}"}, "steps": args.steps,
            "warmup": args.warmup, "hbm_peak": HBM_PEAK_GBPS}
@@ -186,7 +211,7 @@ def bench_ceilings(args, cfg, torch, B, synth, dev):
         for r in range(args.warmup + args.steps):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
-            B.qesgd_stream_probe(pattern, *bufs, n, stream)
+            probe(pattern, *bufs, n, stream)
             e1.record(stream)
             e1.synchronize()
             if r >= args.warmup:

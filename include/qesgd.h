@@ -75,8 +75,7 @@ enum {
     QESGD_ERR_HIP = -10,       /* a launch failed; see qesgd_last_hip_error()          */
     QESGD_ERR_BITS = -11,      /* b not in {2,4,8,16}                                  */
     QESGD_ERR_DELTA = -12,     /* delta not a positive finite number                   */
-    QESGD_ERR_ROUNDS = -13,    /* rounds == 0                                          */
-    QESGD_ERR_PATTERN = -14    /* unknown probe pattern                                */
+    QESGD_ERR_ROUNDS = -13     /* rounds == 0                                          */
 };
 
 enum { QESGD_NORM_L2 = 0, QESGD_NORM_MAX = 1 };
@@ -172,22 +171,6 @@ int qesgd_dequantize_fixed_update(const void* codes, uint64_t d, float delta, ui
 /* End of an epoch (Alg. 3, last step; equal to Alg. 2's mean of the iterates u_{t,k}):
  * w_i += zsum_i / rounds, then zsum_i = 0 for the next epoch (z starts again at 0). */
 int qesgd_epoch_commit(float* w_inout, float* zsum_inout, uint32_t rounds, uint64_t d, void* stream);
-
-/* Measurement aid, not a step of the method: plain streaming kernels with the memory-access
- * mixes of the two hot kernels and no arithmetic to speak of, so that a benchmark can set the
- * kernels' throughput against what the same machine reaches on the same footprint.  n floats,
- * a multiple of 4096; all pointers device memory, 16-byte aligned; unused ones may be NULL.
- *   QESGD_PROBE_READ          reads a[n] with the quantiser's access pattern (a lane owns 32
- *                             bytes); b must be given (n floats) and is not written for
- *                             ordinary data.
- *   QESGD_PROBE_COPY          b[n] = a[n], 16 bytes per lane.
- *   QESGD_PROBE_QUANTIZE_MIX  reads a[n] like the quantiser and writes n/32 words to each of b
- *                             and c: the sign and level planes at one level bit.
- *   QESGD_PROBE_UPDATE_MIX    reads a[n], b[n]; writes c[n], d[n], e[n], 16 bytes per lane: the
- *                             fp32 traffic of the fused update. */
-enum { QESGD_PROBE_READ = 0, QESGD_PROBE_COPY = 1, QESGD_PROBE_QUANTIZE_MIX = 2, QESGD_PROBE_UPDATE_MIX = 3 };
-int qesgd_stream_probe(uint32_t pattern, const float* a, float* b, float* c, float* d, float* e,
-                       uint64_t n, void* stream);
 
 const char* qesgd_strerror(int code);
 /* hipError_t (as int) of the last failed launch on the calling thread, 0 if none. */

@@ -23,7 +23,7 @@ NORM_MAX = 1
 OK = 0
 ERR_NULL, ERR_DIM, ERR_LEVELS, ERR_BUCKET, ERR_WORKERS = -1, -2, -3, -4, -5
 ERR_NORM_KIND, ERR_ALIGN, ERR_STRIDE, ERR_WORKSPACE, ERR_HIP = -6, -7, -8, -9, -10
-ERR_BITS, ERR_DELTA, ERR_ROUNDS, ERR_PATTERN = -11, -12, -13, -14
+ERR_BITS, ERR_DELTA, ERR_ROUNDS = -11, -12, -13
 
 
 class QesgdError(RuntimeError):
@@ -85,8 +85,6 @@ def lib():
         L.qesgd_dequantize_fixed_update.restype = C.c_int
         L.qesgd_epoch_commit.argtypes = [vp, vp, u32, u64, vp]
         L.qesgd_epoch_commit.restype = C.c_int
-        L.qesgd_stream_probe.argtypes = [u32, vp, vp, vp, vp, vp, u64, vp]
-        L.qesgd_stream_probe.restype = C.c_int
         L.qesgd_strerror.argtypes = [C.c_int]
         L.qesgd_strerror.restype = C.c_char_p
         L.qesgd_last_hip_error.argtypes = []
@@ -179,14 +177,6 @@ def qesgd_dequantize_fixed_update(codes, d, delta, b, w_snap, z_out, u_out, zsum
 def qesgd_epoch_commit(w_inout, zsum_inout, rounds, d, stream=None):
     _check(lib().qesgd_epoch_commit(_ptr(w_inout), _ptr(zsum_inout), int(rounds), int(d), _stream(stream)),
            "qesgd_epoch_commit")
-
-
-PROBE_READ, PROBE_COPY, PROBE_QUANTIZE_MIX, PROBE_UPDATE_MIX = 0, 1, 2, 3
-
-
-def qesgd_stream_probe(pattern, a, b, c, d, e, n, stream=None):
-    _check(lib().qesgd_stream_probe(int(pattern), _ptr(a), _ptr(b), _ptr(c), _ptr(d), _ptr(e), int(n),
-                                    _stream(stream)), "qesgd_stream_probe")
 
 
 def qesgd_abi_version() -> int:

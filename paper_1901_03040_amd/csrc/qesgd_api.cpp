@@ -216,18 +216,6 @@ int qesgd_epoch_commit(float* w_inout, float* zsum_inout, uint32_t rounds, uint6
     return launch_epoch_commit(w_inout, zsum_inout, rounds, d, (hipStream_t)stream);
 }
 
-int qesgd_stream_probe(uint32_t pattern, const float* a, float* b, float* c, float* d, float* e,
-                       uint64_t n, void* stream) {
-    if (pattern > QESGD_PROBE_UPDATE_MIX) return QESGD_ERR_PATTERN;
-    if (!a || !b) return QESGD_ERR_NULL;
-    if (pattern >= QESGD_PROBE_QUANTIZE_MIX && !c) return QESGD_ERR_NULL;
-    if (pattern == QESGD_PROBE_UPDATE_MIX && (!d || !e)) return QESGD_ERR_NULL;
-    if (n == 0 || n % 4096u != 0 || n >= (1ull << 40)) return QESGD_ERR_DIM;
-    if (!aligned(a, 16) || !aligned(b, 16) || !aligned(c, 16) || !aligned(d, 16) || !aligned(e, 16))
-        return QESGD_ERR_ALIGN;
-    return launch_stream_probe(pattern, a, b, c, d, e, n, (hipStream_t)stream);
-}
-
 const char* qesgd_strerror(int code) {
     switch (code) {
         case QESGD_OK: return "ok";
@@ -243,7 +231,6 @@ const char* qesgd_strerror(int code) {
         case QESGD_ERR_HIP: return "kernel launch failed (see qesgd_last_hip_error)";
         case QESGD_ERR_BITS: return "b must be one of 2, 4, 8, 16";
         case QESGD_ERR_DELTA: return "delta must be a positive finite number";
-        case QESGD_ERR_PATTERN: return "probe pattern must be one of QESGD_PROBE_*";
         case QESGD_ERR_ROUNDS: return "rounds must be at least 1";
         default: return "unknown error code";
     }

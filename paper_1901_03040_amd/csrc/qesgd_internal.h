@@ -71,9 +71,6 @@ int launch_dequantize_fixed_update(const void* codes, uint64_t d, float delta, u
                                    float* z, float* u, float* zsum, hipStream_t stream);
 int launch_epoch_commit(float* w, float* zsum, uint32_t rounds, uint64_t d, hipStream_t stream);
 
-int launch_stream_probe(uint32_t pattern, const float* a, float* b, float* c, float* d, float* e, uint64_t n,
-                        hipStream_t stream);
-
 void set_last_hip_error(int e);
 
 }  // namespace qesgd

@@ -66,29 +66,40 @@ def test_sixty_four_workers_with_center(oracle, B):
     run_and_compare(oracle, B, slab.cuda(), 4, 1024, 3, 9, K=K, center=c.cuda(), d=d)
 
 
-def test_stream_probe_kernels_stay_in_their_buffers(B):
-    """The measurement-aid kernels: copy and update mix give the expected values, the quantiser
-    mix writes exactly n/32 words per plane, and nothing beyond the stated sizes is touched."""
+def test_bench_probe_kernels_stay_in_their_buffers():
+    """The benchmark's plain streaming kernels (their own shared object, not part of the library):
+    copy and update mix give the expected values, the packed mixes write exactly the stated sizes,
+    and nothing beyond them is touched."""
+    import bench
+    probe = bench.load_probe()
+    st = torch.cuda.current_stream()
     n = 3 * 4096
     g = torch.Generator(device="cuda").manual_seed(1)
     a = torch.randn(n + 64, generator=g, device="cuda")
     b = torch.randn(n + 64, generator=g, device="cuda")
     guard = 123.0
     c, d, e = (torch.full((n + 64,), guard, device="cuda") for _ in range(3))
-    B.qesgd_stream_probe(B.PROBE_UPDATE_MIX, a, b, c, d, e, n)
+    probe(bench.PROBE_UPDATE_MIX, a, b, c, d, e, n, st)
     torch.cuda.synchronize()
     assert torch.equal(c[:n], a[:n]) and torch.equal(e[:n], b[:n]) and torch.equal(d[:n], a[:n] + b[:n])
     assert all(bool((t[n:] == guard).all()) for t in (c, d, e))
     c.fill_(guard)
-    B.qesgd_stream_probe(B.PROBE_COPY, a, c, None, None, None, n)
+    probe(bench.PROBE_COPY, a, c, None, None, None, n, st)
     torch.cuda.synchronize()
     assert torch.equal(c[:n], a[:n]) and bool((c[n:] == guard).all())
     p0 = torch.full((n // 32 + 16,), guard, device="cuda")
     p1 = torch.full((n // 32 + 16,), guard, device="cuda")
-    B.qesgd_stream_probe(B.PROBE_QUANTIZE_MIX, a, p0, p1, None, None, n)
+    probe(bench.PROBE_QUANTIZE_MIX, a, p0, p1, None, None, n, st)
+    codes = torch.full((n // 4 + 16,), guard, device="cuda")
+    probe(bench.PROBE_BYTE_CODES_MIX, a, codes, None, None, None, n, st)
     before = b.clone()
-    B.qesgd_stream_probe(B.PROBE_READ, a, b, None, None, None, n)
+    probe(bench.PROBE_READ, a, b, None, None, None, n, st)
     torch.cuda.synchronize()
     assert bool((p0[n // 32:] == guard).all()) and bool((p1[n // 32:] == guard).all())
     assert not bool((p0[:n // 32] == guard).any())
+    assert bool((codes[n // 4:] == guard).all())
     assert torch.equal(b, before)
+    with pytest.raises(RuntimeError):
+        probe(7, a, b, None, None, None, n, st)
+    with pytest.raises(RuntimeError):
+        probe(bench.PROBE_COPY, a, b, None, None, None, n + 1, st)
