@@ -58,8 +58,9 @@
 extern "C" {
 #endif
 
-#define QESGD_ABI_VERSION 1u
+#define QESGD_ABI_VERSION 2u
 #define QESGD_MAX_WORKERS 64u
+#define QESGD_NOALLOC_SCRATCH_BYTES (4u << 20)
 
 enum {
     QESGD_OK = 0,
@@ -75,7 +76,8 @@ enum {
     QESGD_ERR_HIP = -10,       /* a launch failed; see qesgd_last_hip_error()          */
     QESGD_ERR_BITS = -11,      /* b not in {2,4,8,16}                                  */
     QESGD_ERR_DELTA = -12,     /* delta not a positive finite number                   */
-    QESGD_ERR_ROUNDS = -13     /* rounds == 0                                          */
+    QESGD_ERR_ROUNDS = -13,    /* rounds == 0                                          */
+    QESGD_ERR_SCRATCH = -14    /* the shape needs more than QESGD_NOALLOC_SCRATCH_BYTES */
 };
 
 enum { QESGD_NORM_L2 = 0, QESGD_NORM_MAX = 1 };
@@ -128,6 +130,25 @@ int qesgd_quantize_pack_batched(const float* x_slab, uint64_t x_stride, const fl
                                 uint64_t seed, uint32_t round, uint32_t K,
                                 void* packed_slab, uint64_t packed_stride,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* qesgd_quantize_pack_batched for callers that can neither allocate nor bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same results bit for bit, no workspace: the partial sums of wide buckets go to a
+ * QESGD_NOALLOC_SCRATCH_BYTES array that lives in the library's device image, one copy per GPU,
+ * held until the process ends.  The call allocates and frees nothing.
+ *   - Shapes with qesgd_workspace_bytes(d, s, bucket, K) > QESGD_NOALLOC_SCRATCH_BYTES are rejected
+ *     with QESGD_ERR_SCRATCH before any HIP call (the limit is K * n_buckets * padded bucket
+ *     <= 2^32 coordinates; shapes that need no workspace are never rejected for it).
+ *   - The device that is current at the call must be the one `stream` belongs to; the first call
+ *     on a device that needs the scratch looks its address up (hipGetSymbolAddress), so make that
+ *     call once before capturing a graph.
+ *   - All calls on one GPU share the array: calls that overlap in time on one GPU (two streams,
+ *     two threads) race on it.  Nothing in it has to be cleared between calls: every partial sum
+ *     a call reads was written by that call. */
+int qesgd_quantize_pack_batched_noalloc(const float* x_slab, uint64_t x_stride, const float* center,
+                                        uint64_t d, uint32_t s, uint64_t bucket, uint32_t norm_kind,
+                                        uint64_t seed, uint32_t round, uint32_t K,
+                                        void* packed_slab, uint64_t packed_stride, void* stream);
 
 /* Server side (Alg. 3, server task: the sum over the p workers and its scaling):
  *   zbar[i] = ( sum_{k=0}^{K-1} +-level_{k,i} * (norm_{k,b(i)}/(s-1)) ) / K,

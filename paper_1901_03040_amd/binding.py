@@ -23,7 +23,8 @@ NORM_MAX = 1
 OK = 0
 ERR_NULL, ERR_DIM, ERR_LEVELS, ERR_BUCKET, ERR_WORKERS = -1, -2, -3, -4, -5
 ERR_NORM_KIND, ERR_ALIGN, ERR_STRIDE, ERR_WORKSPACE, ERR_HIP = -6, -7, -8, -9, -10
-ERR_BITS, ERR_DELTA, ERR_ROUNDS = -11, -12, -13
+ERR_BITS, ERR_DELTA, ERR_ROUNDS, ERR_SCRATCH = -11, -12, -13, -14
+NOALLOC_SCRATCH_BYTES = 4 << 20
 
 
 class QesgdError(RuntimeError):
@@ -73,6 +74,9 @@ def lib():
         L.qesgd_quantize_pack_batched.argtypes = [vp, u64, vp, u64, u32, u64, u32, u64, u32, u32,
                                                   vp, u64, vp, sz, vp]
         L.qesgd_quantize_pack_batched.restype = C.c_int
+        L.qesgd_quantize_pack_batched_noalloc.argtypes = [vp, u64, vp, u64, u32, u64, u32, u64, u32, u32,
+                                                          vp, u64, vp]
+        L.qesgd_quantize_pack_batched_noalloc.restype = C.c_int
         L.qesgd_unpack_aggregate.argtypes = [vp, u64, u32, u64, u32, u64, vp, vp]
         L.qesgd_unpack_aggregate.restype = C.c_int
         L.qesgd_apply_update.argtypes = [vp, vp, vp, vp, u64, vp]
@@ -143,6 +147,14 @@ def qesgd_quantize_pack_batched(x_slab, x_stride, center, d, s, bucket, norm_kin
                                              int(bucket), int(norm_kind), int(seed), int(rnd), int(K),
                                              _ptr(packed_slab), int(packed_stride), _ptr(workspace),
                                              ws_bytes, _stream(stream)), "qesgd_quantize_pack_batched")
+
+
+def qesgd_quantize_pack_batched_noalloc(x_slab, x_stride, center, d, s, bucket, norm_kind, seed, rnd, K,
+                                        packed_slab, packed_stride, stream=None):
+    _check(lib().qesgd_quantize_pack_batched_noalloc(_ptr(x_slab), int(x_stride), _ptr(center), int(d), int(s),
+                                                     int(bucket), int(norm_kind), int(seed), int(rnd), int(K),
+                                                     _ptr(packed_slab), int(packed_stride), _stream(stream)),
+           "qesgd_quantize_pack_batched_noalloc")
 
 
 def qesgd_unpack_aggregate(packed_slab, packed_stride, K, d, s, bucket, zbar, stream=None):

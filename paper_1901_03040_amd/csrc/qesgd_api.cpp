@@ -68,7 +68,7 @@ static int quantize_common(const float* x, uint64_t x_stride, const float* cente
                            uint32_t s, uint64_t bucket, uint32_t norm_kind, uint64_t seed,
                            uint32_t round, uint32_t worker0, uint32_t K, void* packed,
                            uint64_t packed_stride, void* workspace, size_t workspace_bytes,
-                           void* stream) {
+                           void* stream, bool static_workspace = false) {
     if (!x || !packed) return QESGD_ERR_NULL;
     Shape sh;
     const int rc = make_shape(d, s, bucket, &sh);
@@ -82,7 +82,17 @@ static int quantize_common(const float* x, uint64_t x_stride, const float* cente
         if (packed_stride < sh.lay.bytes_per_worker || (packed_stride % 256) != 0) return QESGD_ERR_STRIDE;
     }
     const size_t need = workspace_floats(sh, K) * sizeof(float);
-    if (need > 0 && (!workspace || workspace_bytes < need)) return QESGD_ERR_WORKSPACE;
+    if (static_workspace) {
+        if (need > QESGD_NOALLOC_SCRATCH_BYTES) return QESGD_ERR_SCRATCH;
+        if (need > 0) {
+            float* ptr = nullptr;
+            const int src = static_scratch(&ptr);
+            if (src != QESGD_OK) return src;
+            workspace = ptr;
+        }
+    } else if (need > 0 && (!workspace || workspace_bytes < need)) {
+        return QESGD_ERR_WORKSPACE;
+    }
     QuantizeArgs a{};
     a.x = x;
     a.x_stride = x_stride;
@@ -160,6 +170,14 @@ int qesgd_quantize_pack_batched(const float* x_slab, uint64_t x_stride, const fl
                            packed_slab, packed_stride, workspace, workspace_bytes, stream);
 }
 
+int qesgd_quantize_pack_batched_noalloc(const float* x_slab, uint64_t x_stride, const float* center,
+                                        uint64_t d, uint32_t s, uint64_t bucket, uint32_t norm_kind,
+                                        uint64_t seed, uint32_t round, uint32_t K, void* packed_slab,
+                                        uint64_t packed_stride, void* stream) {
+    return quantize_common(x_slab, x_stride, center, d, s, bucket, norm_kind, seed, round, 0, K,
+                           packed_slab, packed_stride, nullptr, 0, stream, true);
+}
+
 int qesgd_unpack_aggregate(const void* packed_slab, uint64_t packed_stride, uint32_t K, uint64_t d,
                            uint32_t s, uint64_t bucket, float* zbar, void* stream) {
     return aggregate_common(packed_slab, packed_stride, K, d, s, bucket, nullptr, zbar, nullptr,
@@ -232,6 +250,7 @@ const char* qesgd_strerror(int code) {
         case QESGD_ERR_BITS: return "b must be one of 2, 4, 8, 16";
         case QESGD_ERR_DELTA: return "delta must be a positive finite number";
         case QESGD_ERR_ROUNDS: return "rounds must be at least 1";
+        case QESGD_ERR_SCRATCH: return "shape needs more scratch than the no-allocation entry point holds (4 MiB)";
         default: return "unknown error code";
     }
 }

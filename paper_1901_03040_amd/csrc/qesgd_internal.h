@@ -19,6 +19,9 @@ constexpr uint32_t kChunk = kLaneElems * kWaveSize;   // 512
 constexpr uint64_t kMaxSinglePassBucket = 32768;
 // Tile of the partial-sum pass used for larger buckets.
 constexpr uint64_t kPartialTile = 4096;
+// Floats of the per-GPU static scratch behind qesgd_quantize_pack_batched_noalloc (4 MiB): one
+// partial sum per 4096 padded coordinates, i.e. K * n_buckets * padded_bucket <= 2^32.
+constexpr size_t kStaticScratchFloats = QESGD_NOALLOC_SCRATCH_BYTES / sizeof(float);
 
 struct Shape {
     uint64_t d;
@@ -61,6 +64,8 @@ struct AggregateArgs {
 };
 
 int launch_quantize(const Shape& sh, const QuantizeArgs& a);
+// Device address of the current GPU's static scratch (kStaticScratchFloats floats).
+int static_scratch(float** out);
 int launch_aggregate(const Shape& sh, const AggregateArgs& a);
 int launch_apply_update(const float* w, const float* zbar, float* u, float* zsum, uint64_t d,
                         hipStream_t stream);

@@ -25,8 +25,15 @@
 //                         buckets wider than kMaxSinglePassBucket: per-tile tree
 //                         sums into the workspace, the rest of each bucket's
 //                         tree, then the quantiser with the scale read back.
+#include <mutex>
+
 #include "qesgd_device.h"
 #include "qesgd_internal.h"
+
+// Scratch of the entry point that allocates nothing: the partial sums of the two-pass path for
+// callers that cannot bring a workspace.  One copy per GPU, held until the process ends; every
+// call on a GPU shares it.  In host code this name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) float scratch[qesgd::kStaticScratchFloats];
 
 namespace qesgd {
 namespace {
@@ -733,7 +740,36 @@ int check_launch() {
     return QESGD_OK;
 }
 
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};     // device address of `scratch` on each GPU, looked up once
+
 }  // namespace
+
+// Device address of the current GPU's copy of `scratch`.  The first call on a device asks the
+// runtime for the address (each GPU holds its own copy at its own address); later calls read
+// the table.
+int static_scratch(float** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+    if (e != hipSuccess) {
+        set_last_hip_error((int)e);
+        return QESGD_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            set_last_hip_error((int)(e != hipSuccess ? e : hipErrorInvalidSymbol));
+            return QESGD_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = static_cast<float*>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return QESGD_OK;
+}
 
 int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
     QParams p{};

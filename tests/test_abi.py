@@ -25,12 +25,12 @@ def test_exports_every_declared_symbol(B):
     assert len(names) >= 10
     for n in names:
         assert hasattr(B.lib(), n), n
-    assert B.qesgd_abi_version() == 1
+    assert B.qesgd_abi_version() == 2
     assert B.qesgd_last_hip_error() == 0
 
 
 def test_error_strings(B):
-    for code in range(0, -14, -1):
+    for code in range(0, -15, -1):
         assert B.strerror(code) and "unknown" not in B.strerror(code)
     assert "unknown" in B.strerror(-99)
 
@@ -109,6 +109,22 @@ def test_quantize_argument_errors(B):
     assert _rc_quant_b(B, stride=4098) == B.ERR_STRIDE
     assert _rc_quant_b(B, pstride=256) == B.ERR_STRIDE
     assert _rc_quant_b(B, pstride=(1 << 20) + 16) == B.ERR_STRIDE
+
+
+def test_noalloc_argument_errors(B):
+    """The no-allocation form rejects bad arguments and shapes beyond its scratch before any HIP call."""
+    L = B.lib()
+    x, pk = 0x10000, 0x20000
+    f = L.qesgd_quantize_pack_batched_noalloc
+    assert f(None, 4096, None, 4096, 4, 512, 0, 1, 0, 2, pk, 1 << 20, None) == B.ERR_NULL
+    assert f(x, 4096, None, 4096, 4, 512, 0, 1, 0, 0, pk, 1 << 20, None) == B.ERR_WORKERS
+    assert f(x, 4000, None, 4096, 4, 512, 0, 1, 0, 2, pk, 1 << 20, None) == B.ERR_STRIDE
+    assert f(x, 4096, None, 4096, 4, 512, 2, 1, 0, 2, pk, 1 << 20, None) == B.ERR_NORM_KIND
+    d = 1 << 31                                      # one bucket: 2^31 / 4096 partial sums per worker
+    assert B.qesgd_workspace_bytes(d, 2, d, 2) == B.NOALLOC_SCRATCH_BYTES
+    assert B.qesgd_workspace_bytes(d, 2, d, 3) > B.NOALLOC_SCRATCH_BYTES
+    assert f(x, d, None, d, 2, d, 0, 1, 0, 3, pk, 1 << 33, None) == B.ERR_SCRATCH
+    assert "scratch" in B.strerror(B.ERR_SCRATCH)
 
 
 def test_aggregate_argument_errors(B):
