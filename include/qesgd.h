@@ -16,8 +16,10 @@
  *     (a hipStream_t passed as void*, NULL = the default stream) and return
  *     without synchronising.  Argument errors are detected before any HIP call,
  *     so they can be exercised on a machine without a GPU.
- *   - Return value: QESGD_OK (0) or a negative QESGD_ERR_* code; nothing has
- *     been enqueued when an error is returned.
+ *   - Return value: QESGD_OK (0) or a negative QESGD_ERR_* code.  Nothing has
+ *     been enqueued when an argument error is returned; QESGD_ERR_HIP reports a
+ *     failed launch, and the launches of the same call that preceded it (the
+ *     partial-sum passes of wide buckets) may already be in the stream.
  *   - Inputs must be finite; NaN / Inf give unspecified codes.
  *   - Arithmetic is IEEE binary32, round to nearest even, no fused multiply-add,
  *     subnormals kept; results do not depend on the launch geometry.
@@ -65,7 +67,9 @@ extern "C" {
 enum {
     QESGD_OK = 0,
     QESGD_ERR_NULL = -1,       /* a required pointer is NULL                          */
-    QESGD_ERR_DIM = -2,        /* d == 0 or d >= 2^40                                 */
+    QESGD_ERR_DIM = -2,        /* d == 0 or d >= 2^40, or the launch would need 2^31
+                                  workgroups or more (one per 4096..65536 coordinates
+                                  and worker: e.g. d = 2^38 with K = 64)              */
     QESGD_ERR_LEVELS = -3,     /* s not 2,4,8,16,32,64,128,256 or 65536                */
     QESGD_ERR_BUCKET = -4,     /* bucket == 0, or bucket < d and bucket % 32 != 0      */
     QESGD_ERR_WORKERS = -5,    /* K == 0 or K > QESGD_MAX_WORKERS                      */

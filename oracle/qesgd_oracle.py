@@ -162,6 +162,7 @@ def quantize_pack(x, s, bucket, seed, rnd, worker, center=None, norm_kind=0):
     x = _f32(x)
     c = None if center is None else _f32(center)
     d = x.size
+    assert c is None or c.size >= d, "center is shorter than x"
     nb, nsw, nlw, _, _ = shape(d, s, bucket)
     norms = np.empty(nb, dtype=np.float32)
     sw = np.empty(nsw, dtype=np.uint32)
@@ -195,8 +196,10 @@ def apply_update(w_snap, zbar, zsum=None):
     """-> (u, zsum_new or None); zsum is not modified in place."""
     w = _f32(w_snap)
     z = _f32(zbar)
+    assert z.size == w.size, "zbar and w_snap differ in length"
     u = np.empty_like(w)
     zs = None if zsum is None else _f32(zsum).copy()
+    assert zs is None or zs.size == w.size, "zsum and w_snap differ in length"
     lib().qo_apply_update(_p(w), _p(z), _p(u), _p(zs), w.size)
     return u, zs
 
@@ -205,6 +208,7 @@ def epoch_commit(w, zsum, rounds):
     """-> (w_next, zsum_reset): w + zsum / rounds, and the zeroed running sum."""
     w = _f32(w).copy()
     zs = _f32(zsum).copy()
+    assert zs.size == w.size, "zsum and w differ in length"
     lib().qo_epoch_commit(_p(w), _p(zs), int(rounds), w.size)
     return w, zs
 
@@ -217,6 +221,7 @@ def quantize_fixed(x, delta, b, seed, rnd, worker, center=None):
     """Fixed-grid quantiser of Eq. (1)-(2): -> codes, ceil(d*b/32) uint32 words."""
     x = _f32(x)
     c = None if center is None else _f32(center)
+    assert c is None or c.size >= x.size, "center is shorter than x"
     codes = np.empty((x.size * b + 31) // 32, dtype=np.uint32)
     rc = lib().qo_quantize_fixed(_p(x), _p(c), x.size, float(np.float32(delta)), int(b), int(seed), int(rnd),
                                  int(worker), _p(codes))
@@ -228,10 +233,12 @@ def quantize_fixed(x, delta, b, seed, rnd, worker, center=None):
 def dequantize_fixed_update(codes, d, delta, b, w_snap=None, zsum=None):
     """-> (z, u or None, zsum_new or None)."""
     codes = np.ascontiguousarray(codes, dtype=np.uint32)
+    assert codes.size >= (d * b + 31) // 32, "codes is shorter than ceil(d*b/32) words"
     z = np.empty(d, dtype=np.float32)
     w = None if w_snap is None else _f32(w_snap)
     u = None if w is None else np.empty(d, dtype=np.float32)
     zs = None if zsum is None else _f32(zsum).copy()
+    assert (w is None or w.size == d) and (zs is None or zs.size == d), "w_snap / zsum length differs from d"
     rc = lib().qo_dequantize_fixed_update(_p(codes), int(d), float(np.float32(delta)), int(b), _p(w), _p(z), _p(u), _p(zs))
     if rc != 0:
         raise ValueError("qo_dequantize_fixed_update rejected its arguments")

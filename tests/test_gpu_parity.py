@@ -116,6 +116,11 @@ def test_degenerate_inputs(oracle, B):
         x[4096] = 1e-45
         lay, packed = gpu_quantize(B, x.cuda(), s, bucket, 1, 0, 0)
         assert_codes_equal(oracle, B, x.numpy(), s, bucket, 1, 0, 0, lay, packed[0])
+        # max norm: the subnormal bucket keeps its scale, whose reciprocal overflows (levels 0)
+        lay, packed = gpu_quantize(B, x.cuda(), s, bucket, 1, 0, 0, norm_kind=1)
+        assert_codes_equal(oracle, B, x.numpy(), s, bucket, 1, 0, 0, lay, packed[0], norm_kind=1)
+        norms, _, lw = host_planes(B, packed[0], lay)
+        assert norms[2] == np.float32(1e-41) and norms[2] > 0
 
 
 def test_padding_bits_zero_and_gaps_untouched(oracle, B):
@@ -178,6 +183,42 @@ def test_batched_equals_single_calls_and_streams_are_keyed(oracle, B, S):
                                   other.stride(0))
     torch.cuda.synchronize()
     assert torch.equal(again, packed) and not torch.equal(other, packed)
+
+
+@pytest.mark.parametrize("d,bucket,s,K,norm_kind,with_center", [
+    (100_000, 100_000, 16, 3, 0, False),      # one bucket, dense tiles + ragged tile
+    (150_000, 65_536, 4, 4, 0, False),        # three wide power-of-two buckets
+    (200_003, 48_000, 256, 3, 0, False),      # wide bucket that is not a power of two (guarded passes only)
+    (150_000, 65_536, 2, 3, 1, False),        # max norm
+    (300_001, 262_144, 16, 5, 0, True),       # with center
+    (100_000, 1 << 30, 32, 3, 0, False),      # level width that does not divide a word
+    (140_000, 1 << 30, 128, 4, 1, True)])
+def test_wide_buckets_batched(oracle, B, d, bucket, s, K, norm_kind, with_center):
+    """Buckets wider than one workgroup's tile (the scale takes a pass of its own) for several
+    workers in one call: every worker against the oracle and against K single calls."""
+    g = torch.Generator(device="cpu").manual_seed(d + K)
+    stride = (d + 63) // 64 * 64
+    slab = torch.zeros(K, stride)
+    slab[:, :d] = torch.randn(K, d, generator=g) * 1e-3 * (1 + torch.arange(K))[:, None]
+    c = (torch.randn(d, generator=g) * 1e-3) if with_center else None
+    lay = B.qesgd_layout_query(d, s, bucket)
+    wsb = B.qesgd_workspace_bytes(d, s, bucket, K)
+    assert wsb > 0 and wsb == K * B.qesgd_workspace_bytes(d, s, bucket, 1)
+    ws = torch.full((wsb // 4,), float("nan"), device="cuda")
+    packed = B.alloc_packed(lay, K)
+    packed.fill_(0xA5)
+    dslab, dc = slab.cuda(), None if c is None else c.cuda()
+    B.qesgd_quantize_pack_batched(dslab, stride, dc, d, s, bucket, norm_kind, 21, 2, K, packed, packed.stride(0), ws)
+    torch.cuda.synchronize()
+    for k in range(K):
+        assert_codes_equal(oracle, B, slab[k, :d].numpy(), s, bucket, 21, 2, k, lay, packed[k],
+                           center_host=None if c is None else c.numpy(), norm_kind=norm_kind)
+        single = B.alloc_packed(lay, 1)
+        single.fill_(0xA5)
+        ws1 = torch.full((wsb // 4 // K,), float("nan"), device="cuda")
+        B.qesgd_quantize_pack(dslab[k], dc, d, s, bucket, norm_kind, 21, 2, k, single, ws1)
+        torch.cuda.synchronize()
+        assert torch.equal(single[0], packed[k]), k
 
 
 @pytest.mark.parametrize("name,d", [("cfg1", 16_384), ("cfg2", 40_000), ("cfg3", 41_034), ("cfg4", 70_008),

@@ -272,6 +272,38 @@ def test_all_zero_bucket(oracle, s):
     assert norm == 0.0 and not level.any() and not sign.any()      # -0 is not negative
 
 
+def test_scale_whose_reciprocal_overflows(oracle):
+    """A non-zero scale so small that (s-1)/norm is not a finite fp32 number encodes like an
+    all-zero bucket: levels 0, the scale itself and the signs kept.  The overflow threshold is
+    checked in exact rational arithmetic: the quotient rounds to infinity iff it is at least
+    2^128 - 2^103 (half an ulp above the largest finite fp32)."""
+    from fractions import Fraction
+    limit = Fraction(2) ** 128 - Fraction(2) ** 103
+    for s in (2, 16, 256, 65536):
+        for norm in (1e-45, 1e-41, 2.9e-39, 3e-39, 1.17e-38, 7.4e-37, 7.6e-37, 1.9e-34, 2.0e-34, 1e-30):
+            nf = np.float32(norm)
+            got = oracle.inverse_step(nf, s)
+            exact = Fraction(s - 1) / Fraction(float(nf))
+            if exact >= limit:
+                assert got == 0.0, (s, norm)
+            else:
+                assert got > 0.0 and abs(Fraction(got) - exact) <= exact * Fraction(1, 2 ** 24), (s, norm)
+    tiny = np.float32(1e-41)                                   # subnormal
+    v = np.full(40, tiny, np.float32)
+    v[5] = -tiny
+    # L2: the squares underflow to 0, so the scale is 0 as for an all-zero bucket
+    norm, level, sign = oracle.quantize_bucket(v, 64, 0, 256, 1, 0, 0)
+    assert norm == 0.0 and not level.any() and sign[5] == 1 and sign.sum() == 1
+    # max norm: the scale is the subnormal itself, its reciprocal overflows
+    for s in (2, 256):
+        norm, level, sign = oracle.quantize_bucket(v, 64, 0, s, 1, 0, 0, norm_kind=1)
+        assert np.float32(norm) == tiny and not level.any() and sign[5] == 1 and sign.sum() == 1
+    # just above the threshold the bucket quantises normally: max element reaches the top level
+    v = np.full(40, np.float32(1e-36), np.float32)
+    norm, level, sign = oracle.quantize_bucket(v, 64, 0, 256, 1, 0, 0, norm_kind=1)
+    assert np.float32(norm) == np.float32(1e-36) and (level >= 254).all()
+
+
 @pytest.mark.parametrize("s", LEVELS)
 def test_one_hot_reaches_top_level(oracle, s):
     v = np.zeros(32, np.float32)
