@@ -9,6 +9,7 @@ P = packed bytes per worker), per-phase GB/s and parameters/s, the roofline of t
 kernel from HIP events on the launch stream, and the CPU oracle timed on a bounded sample.
 """
 import argparse
+from dataclasses import replace
 import json
 import os
 import sys
@@ -42,16 +43,18 @@ def host_cpu():
     return {"model": model, "online_cpus": os.cpu_count()}
 
 
-def cpu_baseline(cfg, slab, w, lay, budget_elems=1 << 26):
-    """The oracle as it stands, one host thread, on a bucket-aligned prefix of the same workload."""
+def cpu_baseline(cfg, slab, w, lay, center=False, norm_kind=0, budget_elems=1 << 26):
+    """The oracle as it stands, one host thread, on a bucket-aligned prefix of the same workload
+    (the whole vector when the bucket is wider than the budget, or with budget_elems=None)."""
     import numpy as np
     from oracle import qesgd_oracle as oracle
     B = min(cfg.bucket, cfg.d)
-    ds = min(cfg.d, max(B, (budget_elems // B) * B))
+    ds = cfg.d if budget_elems is None else min(cfg.d, max(B, (budget_elems // B) * B))
     host = slab[:, :ds].cpu().numpy()
     wh = w[:ds].cpu().numpy()
     t0 = time.perf_counter()
-    planes = [oracle.quantize_pack(host[k], cfg.s, cfg.bucket, cfg.seed, 0, k) for k in range(cfg.K)]
+    planes = [oracle.quantize_pack(host[k], cfg.s, cfg.bucket, cfg.seed, 0, k, center=wh if center else None,
+                                   norm_kind=norm_kind) for k in range(cfg.K)]
     t1 = time.perf_counter()
     norms = np.stack([p[0] for p in planes])
     sw = np.stack([p[1] for p in planes])
@@ -62,7 +65,7 @@ def cpu_baseline(cfg, slab, w, lay, budget_elems=1 << 26):
     t3 = time.perf_counter()
     nb, nsw, nlw, _, _ = oracle.shape(ds, cfg.s, cfg.bucket)
     P = 4 * (nb + nsw + nlw)
-    qb, ub = cfg.K * (4 * ds + P), cfg.K * P + 20 * ds
+    qb, ub = cfg.K * (4 * ds + P) + (4 * ds if center else 0), cfg.K * P + 20 * ds
     tq, tu = t1 - t0, t3 - t2
     return {
         "value": round((qb + ub) / (tq + tu) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
@@ -72,6 +75,18 @@ def cpu_baseline(cfg, slab, w, lay, budget_elems=1 << 26):
         "quantize_params_per_s": round(cfg.K * ds / tq), "aggregate_update_params_per_s": round(ds / tu),
         "seconds": round(tq + tu, 2), "host": host_cpu(),
     }
+
+
+def quantize_kernels(cfg, args, workspace_bytes):
+    """Names of the kernels one quantize-pack call launches for this shape (what rocprofv3 will list)."""
+    B = min(cfg.bucket, cfg.d)
+    if workspace_bytes:
+        return "k_tile_partials(_fast) + k_finish_norms + k_quantize_pack_pre_fast (two passes, per group of workers)"
+    pow2 = B & (B - 1) == 0
+    m = cfg.s.bit_length() - 1
+    if pow2 and B >= 32 and args.norm == "l2" and 32 % m == 0 and cfg.d >= max(4096, B):
+        return "k_quantize_pack_fast"
+    return "k_quantize_pack"
 
 
 def load_traffic(workload):
@@ -230,6 +245,13 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default: the largest, VGG-16-sized)")
+    ap.add_argument("--bucket", default=None,
+                    help="override the configuration's bucket size: a number (a multiple of 32), or 'whole' "
+                         "for one scale over the whole vector (the two-pass path of wide buckets)")
+    ap.add_argument("--s", type=int, default=None, help="override the configuration's number of levels")
+    ap.add_argument("--norm", default="l2", choices=["l2", "max"], help="bucket scale: L2 norm (default) or max |v|")
+    ap.add_argument("--center", action="store_true",
+                    help="the workers hold x_k = w_t + z_k and the quantiser forms x_k - w_t itself (reads 8 B per coordinate)")
     ap.add_argument("--path", default="qesgd", choices=["qesgd", "fixed"],
                     help="qesgd: bucketed quantize-pack + unpack-aggregate-update (the headline path); "
                          "fixed: the paper-literal fixed-grid quantiser (b = 8) + its fused inverse")
@@ -239,6 +261,9 @@ def main():
                     help="instead of the benchmark, time plain streaming kernels with the hot kernels' "
                          "access mixes on the workload's footprint (practical HBM ceilings of this machine)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-full", action="store_true",
+                    help="time the CPU oracle on the whole workload instead of a 2^26-coordinate prefix "
+                         "(cfg5: about 25 s)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (reference point for --pmc byte counters)")
     args = ap.parse_args()
@@ -257,6 +282,18 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     cfg = synth.by_name(args.config)
+    variant = cfg.name
+    if args.bucket is not None:
+        bucket = cfg.d if args.bucket == "whole" else int(args.bucket)
+        cfg = replace(cfg, bucket=bucket)
+        variant += "_whole" if bucket >= cfg.d else f"_b{bucket}"
+    if args.s is not None:
+        cfg = replace(cfg, s=args.s)
+        variant += f"_s{args.s}"
+    if args.norm == "max":
+        variant += "_max"
+    if args.center:
+        variant += "_center"
     if args.ceilings:
         return bench_ceilings(args, cfg, torch, B, synth, dev)
     if args.path == "fixed":
@@ -264,6 +301,11 @@ def main():
     lay = B.qesgd_layout_query(cfg.d, cfg.s, cfg.bucket)
     slab = synth.worker_slab(cfg, dev)
     w = synth.snapshot(cfg, dev)
+    center = None
+    if args.center:
+        slab[:, :cfg.d] += w          # x_k = w_t + z_k; the kernel quantises fl(x_k - w_t)
+        center = w
+    norm_kind = B.NORM_MAX if args.norm == "max" else B.NORM_L2
     packed = B.alloc_packed(lay, cfg.K, dev)
     zbar = torch.empty(cfg.d, device=dev)
     u = torch.empty(cfg.d, device=dev)
@@ -282,7 +324,7 @@ def main():
     def step(r, events=None):
         if events is not None:
             events[0].record(stream)
-        B.qesgd_quantize_pack_batched(slab, slab.stride(0), None, cfg.d, cfg.s, cfg.bucket, B.NORM_L2,
+        B.qesgd_quantize_pack_batched(slab, slab.stride(0), center, cfg.d, cfg.s, cfg.bucket, norm_kind,
                                       cfg.seed, r, cfg.K, packed, packed.stride(0), ws, stream)
         if events is not None:
             events[1].record(stream)
@@ -307,7 +349,9 @@ def main():
     tu = sorted(e[1].elapsed_time(e[2]) for e in evs)
     tq_avg, tu_avg = sum(tq) / len(tq), sum(tu) / len(tu)
     qb, ub = algorithmic_bytes(cfg, lay)
-    traffic = load_traffic(cfg.name) or {}
+    if args.center:
+        qb += 4 * cfg.d               # w_t is shared by the K workers of one GPU: read once
+    traffic = load_traffic(variant) or {}
 
     def phase(bytes_, ms_avg, ms_sorted, params):
         return {"algorithmic_bytes": bytes_, "ms_avg": round(ms_avg, 4), "ms_median": round(ms_sorted[len(ms_sorted) // 2], 4),
@@ -321,7 +365,7 @@ def main():
 
     def roofline(name):
         ph = phases[name]
-        launches = {"quantize_pack": "k_quantize_pack_fast",
+        launches = {"quantize_pack": quantize_kernels(cfg, args, wsb),
                     "unpack_aggregate_update": "k_unpack_aggregate_update"}[name]
         return {"kernel": launches, "bound": "hbm", "achieved": ph["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": ph["frac_of_hbm_peak"], "traffic": traffic.get(name)}
@@ -331,9 +375,11 @@ def main():
         "value": round((qb + ub) / ms_step / 1e6, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: d={cfg.d} ({cfg.model}), K={cfg.K}, s={cfg.s}, bucket={cfg.bucket}, "
+        "config": {"workload": f"{variant}: d={cfg.d} ({cfg.model}), K={cfg.K}, s={cfg.s}, bucket={cfg.bucket}, "
+                               f"norm {args.norm}, {'x - w_t formed in the kernel, ' if args.center else ''}"
                                f"entries {cfg.entries}, seed {cfg.seed}",
-                   "d": cfg.d, "K": cfg.K, "s": cfg.s, "bucket": cfg.bucket,
+                   "d": cfg.d, "K": cfg.K, "s": cfg.s, "bucket": cfg.bucket, "norm": args.norm,
+                   "center": bool(args.center),
                    "packed_bytes_per_worker": lay.payload_bytes},
         "frac_of_hbm_peak": round((qb + ub) / ms_step / 1e6 / HBM_PEAK_GBPS, 4),
         "params_per_s": round(cfg.K * cfg.d / ms_step * 1e3),
@@ -347,13 +393,13 @@ def main():
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            B.qesgd_quantize_pack_batched(slab, slab.stride(0), None, cfg.d, cfg.s, cfg.bucket, B.NORM_L2,
+            B.qesgd_quantize_pack_batched(slab, slab.stride(0), center, cfg.d, cfg.s, cfg.bucket, norm_kind,
                                           cfg.seed, 0, cfg.K, packed, packed.stride(0), ws)
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            B.qesgd_quantize_pack_batched(slab, slab.stride(0), None, cfg.d, cfg.s, cfg.bucket, B.NORM_L2,
+            B.qesgd_quantize_pack_batched(slab, slab.stride(0), center, cfg.d, cfg.s, cfg.bucket, norm_kind,
                                           cfg.seed, 0, cfg.K, packed, packed.stride(0), ws)
             B.qesgd_unpack_aggregate_update(packed, packed.stride(0), cfg.K, cfg.d, cfg.s, cfg.bucket, w, zbar, u,
                                             zsum)
@@ -366,7 +412,8 @@ def main():
         torch.cuda.synchronize()
         out["graph_replay_ms_per_step"] = round((time.perf_counter() - g0) * 1e3 / args.steps, 4)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, slab, w, lay)
+        out["cpu_baseline"] = cpu_baseline(cfg, slab, w, lay, center=args.center, norm_kind=norm_kind,
+                                           budget_elems=None if args.cpu_full else 1 << 26)
     print(json.dumps(out), flush=True)
 
 

@@ -19,6 +19,9 @@ constexpr uint32_t kChunk = kLaneElems * kWaveSize;   // 512
 constexpr uint64_t kMaxSinglePassBucket = 32768;
 // Tile of the partial-sum pass used for larger buckets.
 constexpr uint64_t kPartialTile = 4096;
+// Input bytes that the two-pass path lets the first pass read before the second pass re-reads
+// them: well inside the 256 MB memory-side cache, which also has to take the packed output.
+constexpr uint64_t kCacheBudgetBytes = 160ull << 20;
 // Floats of the per-GPU static scratch behind qesgd_quantize_pack_batched_noalloc (4 MiB): one
 // partial sum per 4096 padded coordinates, i.e. K * n_buckets * padded_bucket <= 2^32.
 constexpr size_t kStaticScratchFloats = QESGD_NOALLOC_SCRATCH_BYTES / sizeof(float);

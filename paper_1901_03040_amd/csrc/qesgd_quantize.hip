@@ -54,6 +54,7 @@ struct QParams {
     uint32_t tiles_per_worker;   // generic kernel: tiles it covers per worker
     uint32_t full_tiles;         // fast kernels: tiles per worker that lie wholly inside the vector
     uint32_t tail_tiles;         // fast quantize kernel: ragged tiles per worker after those (0 or 1)
+    uint32_t group_workers;      // workers covered by this launch
     uint32_t ws_tiles_per_worker;  // partial sums: workspace entries per worker (nb * N / 4096)
     uint64_t data_tiles;         // partial sums: 4096-slot tiles of a worker that hold coordinates
     uint32_t key0, key1;
@@ -125,6 +126,13 @@ __device__ __forceinline__ float lane_tree(const float (&v)[8]) {
     }
     return fmaxf(fmaxf(fmaxf(fabsf(v[0]), fabsf(v[1])), fmaxf(fabsf(v[2]), fabsf(v[3]))),
                  fmaxf(fmaxf(fabsf(v[4]), fabsf(v[5])), fmaxf(fabsf(v[6]), fabsf(v[7]))));
+}
+
+// The same in-lane tree over 8 values that are already partial results (no squaring).
+template <int KIND>
+__device__ __forceinline__ float lane_tree_of_partials(const float (&q)[8]) {
+    return combine<KIND>(combine<KIND>(combine<KIND>(q[0], q[1]), combine<KIND>(q[2], q[3])),
+                         combine<KIND>(combine<KIND>(q[4], q[5]), combine<KIND>(q[6], q[7])));
 }
 
 // Pairwise tree over up to 16 wave totals parked in LDS; entries beyond `count`
@@ -404,12 +412,18 @@ __device__ __forceinline__ void guarded_tile(const QParams& p, uint32_t k, uint3
     }
 }
 
+// PRE (second pass of a wide bucket): workers and tiles are walked backwards, so that the launch
+// starts with what the partial-sum pass read last and most of it is still in the memory-side cache.
 template <int M, int CH, int KIND, bool PRE>
 __global__ void k_quantize_pack(const QParams p) {
     __shared__ float sm[32];
-    const uint32_t k = blockIdx.x / p.tiles_per_worker;
-    const uint32_t tile = p.tile0 + (blockIdx.x - k * p.tiles_per_worker);
-    guarded_tile<M, CH, KIND, PRE>(p, k, tile, sm);
+    uint32_t k = blockIdx.x / p.tiles_per_worker;
+    uint32_t local = blockIdx.x - k * p.tiles_per_worker;
+    if (PRE) {
+        k = p.group_workers - 1u - k;
+        local = p.tiles_per_worker - 1u - local;
+    }
+    guarded_tile<M, CH, KIND, PRE>(p, k, p.tile0 + local, sm);
 }
 
 // ---------------------------------------------------------------------------
@@ -514,8 +528,28 @@ __global__ void __launch_bounds__(Geo<LOG2N>::NW * 64) k_quantize_pack_fast(cons
     __shared__ float sm[32];
 
     const uint32_t per_worker = p.full_tiles + p.tail_tiles;
-    const uint32_t k = blockIdx.x / per_worker;
-    const uint32_t t = blockIdx.x - k * per_worker;
+    uint32_t k, t;
+    if (CENTER) {
+        // All workers read the same `center`.  Workgroups are handed to the 8 XCDs round-robin by
+        // id, so the K workgroups of one tile get ids 8 apart: they run on one XCD one after the
+        // other, and all but the first find the tile of `center` in that XCD's L2.
+        const uint32_t K = p.group_workers;
+        const uint32_t tiles8 = p.full_tiles & ~7u;
+        const uint32_t span = 8u * K;
+        if (blockIdx.x < (tiles8 >> 3) * span) {
+            const uint32_t g = blockIdx.x / span, r = blockIdx.x - g * span;
+            k = r >> 3;
+            t = g * 8u + (r & 7u);
+        } else {                                          // fewer than 8 tiles left, and the ragged one
+            const uint32_t rest = per_worker - tiles8;
+            const uint32_t r = blockIdx.x - (tiles8 >> 3) * span;
+            k = r / rest;
+            t = tiles8 + (r - k * rest);
+        }
+    } else {
+        k = blockIdx.x / per_worker;
+        t = blockIdx.x - k * per_worker;
+    }
     if (t >= p.full_tiles) {                              // the ragged last tile of the worker (at most one)
         guarded_tile<M, CH, QESGD_NORM_L2, false>(p, k, t, sm);
         return;
@@ -541,6 +575,33 @@ __global__ void __launch_bounds__(Geo<LOG2N>::NW * 64) k_quantize_pack_fast(cons
     process_tile<M, LOG2N>(cx, buf, t, sm);
 }
 
+// Tree sum (or max) of one 4096-slot tile of worker k with every access guarded per lane, left in
+// the workspace.  Tiles of a bucket are consecutive in slot space, so the workspace index of
+// (bucket, tile in bucket) is the tile index.  sm: 4 floats of LDS.
+template <int KIND>
+__device__ __forceinline__ void guarded_partial_tile(const QParams& p, uint32_t k, uint32_t tile, float* sm) {
+    constexpr int CH = 2;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = threadIdx.x >> 6;
+    const float* __restrict__ x = p.x + (uint64_t)k * p.x_stride;
+    const uint64_t slot0 = ((uint64_t)tile * 4 + wave) * (uint64_t)(CH * kChunk) + lane * kLaneElems;
+    float t[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        float v[8];
+        const LaneSpan s = lane_span(slot0 + (uint64_t)c * kChunk, p);
+        load_lane(x, p.center, s, v);
+        t[c] = lane_butterfly<KIND>(lane_tree<KIND>(v), 64);
+    }
+    t[0] = combine<KIND>(t[0], t[1]);
+    if (lane == 0) sm[wave] = t[0];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float total = combine<KIND>(combine<KIND>(sm[0], sm[1]), combine<KIND>(sm[2], sm[3]));
+        p.workspace[(uint64_t)k * p.ws_tiles_per_worker + tile] = total;
+    }
+}
+
 // Buckets wider than kMaxSinglePassBucket, tiles wholly inside the vector (slot == coordinate:
 // power-of-two bucket, or a single bucket).  First pass: tree sum of one 4096-coordinate tile into
 // the workspace.  Last pass: the quantiser with the bucket scale read from the norms plane; a tile
@@ -550,8 +611,13 @@ __global__ void __launch_bounds__(256) k_tile_partials_fast(const QParams p) {
     constexpr int KIND = QESGD_NORM_L2;
     __shared__ float sm[4];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint32_t k = blockIdx.x / p.full_tiles;
-    const uint32_t t = blockIdx.x - k * p.full_tiles;
+    const uint32_t per_worker = p.full_tiles + p.tail_tiles;
+    const uint32_t k = blockIdx.x / per_worker;
+    const uint32_t t = blockIdx.x - k * per_worker;
+    if (t >= p.full_tiles) {                              // the ragged last tile of the worker (at most one)
+        guarded_partial_tile<KIND>(p, k, t, sm);
+        return;
+    }
     const uint32_t lane_off = wave * (2u * kChunk) + lane * kLaneElems;
     float v[2][8];
     load_tile<2, CENTER>(p.x + (uint64_t)k * p.x_stride + (uint64_t)t * kPartialTile,
@@ -566,8 +632,14 @@ __global__ void __launch_bounds__(256) k_tile_partials_fast(const QParams p) {
 template <int M, bool CENTER>
 __global__ void __launch_bounds__(256) k_quantize_pack_pre_fast(const QParams p) {
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint32_t k = blockIdx.x / p.full_tiles;
-    const uint32_t t = blockIdx.x - k * p.full_tiles;
+    const uint32_t per_worker = p.full_tiles + p.tail_tiles;
+    const uint32_t kf = blockIdx.x / per_worker;
+    const uint32_t k = p.group_workers - 1u - kf;                       // backwards: see k_quantize_pack
+    const uint32_t t = per_worker - 1u - (blockIdx.x - kf * per_worker);
+    if (t >= p.full_tiles) {                              // the ragged last tile of the worker (at most one)
+        guarded_tile<M, 2, QESGD_NORM_L2, true>(p, k, t, nullptr);
+        return;
+    }
     unsigned char* __restrict__ out = p.packed + (uint64_t)k * p.packed_stride;
     const float* __restrict__ norms = reinterpret_cast<const float*>(out + p.norms_off);
     uint32_t* __restrict__ signs = reinterpret_cast<uint32_t*>(out + p.signs_off);
@@ -597,56 +669,75 @@ __global__ void __launch_bounds__(256) k_quantize_pack_pre_fast(const QParams p)
 // ---------------------------------------------------------------------------
 template <int KIND>
 __global__ void k_tile_partials(const QParams p) {
-    constexpr int CH = 2;
-    __shared__ float sm[16];
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wave = threadIdx.x >> 6;
+    __shared__ float sm[4];
     const uint32_t k = blockIdx.x / p.tiles_per_worker;
     const uint32_t tile = p.tile0 + (blockIdx.x - k * p.tiles_per_worker);
-    const float* __restrict__ x = p.x + (uint64_t)k * p.x_stride;
-    const uint64_t slot0 = ((uint64_t)tile * 4 + wave) * (uint64_t)(CH * kChunk) + lane * kLaneElems;
-    float t[CH];
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        float v[8];
-        const LaneSpan s = lane_span(slot0 + (uint64_t)c * kChunk, p);
-        load_lane(x, p.center, s, v);
-        t[c] = lane_butterfly<KIND>(lane_tree<KIND>(v), 64);
-    }
-    t[0] = combine<KIND>(t[0], t[1]);
-    if (lane == 0) sm[wave] = t[0];
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const float total = combine<KIND>(combine<KIND>(sm[0], sm[1]), combine<KIND>(sm[2], sm[3]));
-        // tiles of a bucket are consecutive in slot space, so (bucket, tile in bucket) = tile index
-        p.workspace[(uint64_t)k * p.ws_tiles_per_worker + tile] = total;
-    }
+    guarded_partial_tile<KIND>(p, k, tile, sm);
 }
 
-// Finishes the tree of one bucket in place: P leaves, of which only the first `valid` were
-// written (the rest of the padded bucket is +0 and is never read: a node that starts at or
-// beyond `valid` is 0, the identity of both combines).
+// Finishes the tree of one bucket: P leaves (a power of two, >= 16), of which only the first
+// `valid` were written (the rest of the padded bucket is +0, the identity of both combines, and is
+// never read).  One workgroup of 16 waves per (worker, bucket) walks the leaves in tiles of 16384
+// = 16 waves x 2 chunks x 512, each reduced like a tile of the first pass (leaf index bits 0-2 in
+// the lane, 3-8 across lanes, 9 across the two chunks, 10-13 across waves); the tile totals are
+// joined by a binary counter: stack[l] holds the finished subtree of 2^l tiles that waits for its
+// right sibling.
+constexpr uint32_t kFinishTile = 16384;
 template <int KIND>
-__global__ void k_finish_norms(const QParams p, uint64_t P, uint32_t dense) {
+__global__ void __launch_bounds__(1024) k_finish_norms(const QParams p, uint64_t P, uint32_t dense) {
+    __shared__ float sm[2][16];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     const uint64_t kb = blockIdx.x;                     // k*nb + b
     const uint32_t k = (uint32_t)(kb / p.nb);
     const uint64_t b = kb - (uint64_t)k * p.nb;
-    float* ws = p.workspace + kb * P;
+    const float* __restrict__ ws = p.workspace + kb * P;
     uint64_t valid = P;
     if (dense) {
         const uint64_t left = p.data_tiles - b * P;     // buckets before the last are full
         valid = left < P ? left : P;
     }
-    for (uint64_t h = 1; h < P; h <<= 1) {
-        for (uint64_t r = (uint64_t)threadIdx.x * 2 * h; r < valid; r += (uint64_t)blockDim.x * 2 * h) {
-            const float other = (r + h < valid) ? ws[r + h] : 0.0f;
-            ws[r] = combine<KIND>(ws[r], other);
+    const uint64_t iters = (P + kFinishTile - 1) / kFinishTile;          // a power of two
+    float stack[16];
+#pragma unroll
+    for (int l = 0; l < 16; ++l) stack[l] = 0.0f;
+    for (uint64_t it = 0; it < iters; ++it) {
+        float total = 0.0f;
+        const uint64_t base = it * kFinishTile;
+        if (base < valid) {                              // uniform: tiles beyond `valid` are all +0
+            float t2[2];
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const uint64_t j = base + wave * 1024u + (uint32_t)c * kChunk + lane * kLaneElems;
+                float q[8];
+                if (j + 8 <= valid) {
+                    const float4 a0 = *reinterpret_cast<const float4*>(ws + j);
+                    const float4 a1 = *reinterpret_cast<const float4*>(ws + j + 4);
+                    q[0] = a0.x; q[1] = a0.y; q[2] = a0.z; q[3] = a0.w;
+                    q[4] = a1.x; q[5] = a1.y; q[6] = a1.z; q[7] = a1.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) q[e] = (j + e < valid) ? ws[j + e] : 0.0f;
+                }
+                t2[c] = lane_butterfly<KIND>(lane_tree_of_partials<KIND>(q), 64);
+            }
+            float* buf = sm[it & 1u];
+            if (lane == 0) buf[wave] = combine<KIND>(t2[0], t2[1]);
+            __syncthreads();                             // one barrier per tile: the buffers alternate
+            total = lds_tree16<KIND>(buf, 0, 16);
         }
-        __syncthreads();
+#pragma unroll
+        for (int l = 0; l < 16; ++l) {                   // iters <= 2^40 / 4096 / 16384 = 2^14
+            if (((it >> l) & 1u) == 0u) { stack[l] = total; break; }
+            total = combine<KIND>(stack[l], total);
+        }
     }
     if (threadIdx.x == 0) {
+        float result = stack[0];
+#pragma unroll
+        for (int l = 1; l < 16; ++l)
+            if ((iters >> l) & 1u) result = stack[l];
         float* norms = reinterpret_cast<float*>(p.packed + (uint64_t)k * p.packed_stride + p.norms_off);
-        norms[b] = (KIND == QESGD_NORM_L2) ? sqrtf(ws[0]) : ws[0];
+        norms[b] = (KIND == QESGD_NORM_L2) ? sqrtf(result) : result;
     }
 }
 
@@ -791,6 +882,7 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
     p.round = a.round;
     p.worker0 = a.worker0;
     p.smax = (float)(sh.s - 1);
+    p.group_workers = a.K;
 
     const uint64_t slots = sh.nb * sh.N;                 // slot space of one worker
     const bool two_pass = sh.N > kMaxSinglePassBucket;
@@ -818,28 +910,52 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
         p.full_tiles = (uint32_t)full_tiles;
         p.tile0 = (uint32_t)full_tiles;
         p.tiles_per_worker = (uint32_t)(data_tiles - full_tiles);
-        const dim3 fast_grid((uint32_t)(full_tiles * a.K)), tail_grid((uint32_t)((data_tiles - full_tiles) * a.K));
-        if (full_tiles > 0) {
-            if (p.center) hipLaunchKernelGGL(k_tile_partials_fast<true>, fast_grid, block, 0, a.stream, p);
-            else hipLaunchKernelGGL(k_tile_partials_fast<false>, fast_grid, block, 0, a.stream, p);
+        // The second pass re-reads what the first read.  Workers are taken in groups whose input
+        // fits the memory-side cache (all of them at once when everything fits), the partial sums,
+        // the rest of the tree and the quantiser one group after the other, and the quantiser walks
+        // its group backwards: what the first pass read last is read first.
+        const uint64_t worker_bytes = 4u * sh.d;
+        uint32_t group = a.K;
+        if ((uint64_t)a.K * worker_bytes > kCacheBudgetBytes) {
+            const uint64_t fit = kCacheBudgetBytes / worker_bytes;
+            group = fit < 1 ? 1u : (uint32_t)fit;
         }
-        const dim3 finish_grid((uint32_t)(sh.nb * a.K));
-        if (a.norm_kind == QESGD_NORM_L2) {
-            if (data_tiles > full_tiles) hipLaunchKernelGGL(k_tile_partials<QESGD_NORM_L2>, tail_grid, block, 0, a.stream, p);
-            hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_L2>, finish_grid, dim3(256), 0, a.stream, p, P, dense ? 1u : 0u);
-        } else {
-            if (data_tiles > full_tiles) hipLaunchKernelGGL(k_tile_partials<QESGD_NORM_MAX>, tail_grid, block, 0, a.stream, p);
-            hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_MAX>, finish_grid, dim3(256), 0, a.stream, p, P, dense ? 1u : 0u);
-        }
-        int rc = check_launch();
-        if (rc != QESGD_OK) return rc;
-        if (full_tiles > 0) {
-            launch_pre_fast(p, sh.m, (uint32_t)(full_tiles * a.K), a.stream);
+        for (uint32_t k0 = 0; k0 < a.K; k0 += group) {
+            const uint32_t kg = a.K - k0 < group ? a.K - k0 : group;
+            p.x = a.x + (uint64_t)k0 * a.x_stride;
+            p.packed = a.packed + (uint64_t)k0 * a.packed_stride;
+            p.workspace = a.workspace + (uint64_t)k0 * tiles;
+            p.worker0 = a.worker0 + k0;
+            p.group_workers = kg;
+            const dim3 finish_grid((uint32_t)(sh.nb * kg));
+            int rc;
+            if (full_tiles > 0) {
+                // dense tiles unguarded, the ragged last tile of each worker guarded in the same launches
+                p.tail_tiles = (uint32_t)(data_tiles - full_tiles);
+                const dim3 grid((uint32_t)(data_tiles * kg));
+                if (p.center) hipLaunchKernelGGL(k_tile_partials_fast<true>, grid, block, 0, a.stream, p);
+                else hipLaunchKernelGGL(k_tile_partials_fast<false>, grid, block, 0, a.stream, p);
+                hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_L2>, finish_grid, dim3(1024), 0, a.stream, p, P, 1u);
+                rc = check_launch();
+                if (rc != QESGD_OK) return rc;
+                launch_pre_fast(p, sh.m, (uint32_t)(data_tiles * kg), a.stream);
+            } else {
+                const dim3 grid((uint32_t)(data_tiles * kg));
+                if (a.norm_kind == QESGD_NORM_L2) {
+                    hipLaunchKernelGGL(k_tile_partials<QESGD_NORM_L2>, grid, block, 0, a.stream, p);
+                    hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_L2>, finish_grid, dim3(1024), 0, a.stream, p, P, dense ? 1u : 0u);
+                } else {
+                    hipLaunchKernelGGL(k_tile_partials<QESGD_NORM_MAX>, grid, block, 0, a.stream, p);
+                    hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_MAX>, finish_grid, dim3(1024), 0, a.stream, p, P, dense ? 1u : 0u);
+                }
+                rc = check_launch();
+                if (rc != QESGD_OK) return rc;
+                launch_m<2, true>(p, sh.m, a.norm_kind, grid, block, a.stream);
+            }
             rc = check_launch();
             if (rc != QESGD_OK) return rc;
         }
-        if (data_tiles > full_tiles) launch_m<2, true>(p, sh.m, a.norm_kind, tail_grid, block, a.stream);
-        return check_launch();
+        return QESGD_OK;
     }
 
     // Tiles that lie wholly inside the vector go to the fast kernel when the bucket is a

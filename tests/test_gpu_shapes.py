@@ -66,6 +66,21 @@ def test_sixty_four_workers_with_center(oracle, B):
     run_and_compare(oracle, B, slab.cuda(), 4, 1024, 3, 9, K=K, center=c.cuda(), d=d)
 
 
+@pytest.mark.parametrize("K", [1, 3, 8])
+@pytest.mark.parametrize("d,bucket,s", [(4096 * 19 + 100, 512, 16), (8192 * 9 + 8, 8192, 256), (4096 * 8, 4096, 2),
+                                        (4096 * 7 + 4000, 64, 4), (32768 * 8 + 5, 32768, 4)])
+def test_batched_with_center_tile_order(oracle, B, K, d, bucket, s):
+    """With a center the workgroups of a launch take (worker, tile) in an order of their own (the
+    workers of one tile next to each other); every worker's output must not depend on it."""
+    g = torch.Generator(device="cpu").manual_seed(d + K)
+    stride = (d + 63) // 64 * 64
+    slab = torch.zeros(K, stride)
+    c = torch.randn(d, generator=g)
+    slab[:, :d] = c[None, :] + torch.randn(K, d, generator=g) * 1e-3
+    run_and_compare(oracle, B, slab.cuda() if K > 1 else slab[0, :d].contiguous().cuda(), s, bucket, 8, 2, K=K,
+                    center=c.cuda(), d=d)
+
+
 def test_bench_probe_kernels_stay_in_their_buffers():
     """The benchmark's plain streaming kernels (their own shared object, not part of the library):
     copy and update mix give the expected values, the packed mixes write exactly the stated sizes,
