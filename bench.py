@@ -99,6 +99,16 @@ def load_traffic(workload):
     return None
 
 
+def copy_calibration(args, torch, dev):
+    """--copy-calibration: one 1 GiB device-to-device copy, the reference point for --pmc byte counters."""
+    if args.copy_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
+
 def bench_fixed_grid(args, cfg, torch, B, synth, dev):
     """Server-to-worker direction with the quantiser as the paper writes it (Eq. (1)-(2), b = 8, the
     paper's setting): one step = qesgd_quantize_fixed of a d-vector + qesgd_dequantize_fixed_update
@@ -113,6 +123,9 @@ def bench_fixed_grid(args, cfg, torch, B, synth, dev):
     u = torch.empty(d, device=dev)
     zsum = torch.zeros(d, device=dev)
     stream = torch.cuda.current_stream()
+    copy_calibration(args, torch, dev)
+    variant = f"{cfg.name}_fixed_b{b}"
+    traffic = load_traffic(variant) or {}
 
     def step(r, ev=None):
         if ev:
@@ -142,7 +155,7 @@ def bench_fixed_grid(args, cfg, torch, B, synth, dev):
         "value": round((qb + db) / ms_step / 1e6, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name} shape, fixed grid: d={d} ({cfg.model}), b={b}, delta={delta:.3e}, "
+        "config": {"workload": f"{variant}: {cfg.name} shape, fixed grid: d={d} ({cfg.model}), b={b}, delta={delta:.3e}, "
                                f"entries {cfg.entries}, seed {cfg.seed}", "d": d, "b": b},
         "phases": {
             "quantize_fixed": {"algorithmic_bytes": qb, "ms_avg": round(tq, 4), "GBps": round(qb / tq / 1e6, 1),
@@ -156,7 +169,7 @@ def bench_fixed_grid(args, cfg, torch, B, synth, dev):
     dom = "quantize_fixed" if tq >= td else "dequantize_fixed_update"
     out["roofline"] = {"kernel": "k_" + dom, "bound": "hbm", "achieved": out["phases"][dom]["GBps"],
                        "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": out["phases"][dom]["frac_of_hbm_peak"],
-                       "traffic": None}
+                       "traffic": traffic.get(dom)}
     if not args.no_cpu_baseline:
         from oracle import qesgd_oracle as oracle
         ds = min(d, 1 << 26)
@@ -314,12 +327,7 @@ def main():
     ws = torch.empty(max(wsb // 4, 1), dtype=torch.float32, device=dev) if wsb else None
     stream = torch.cuda.current_stream()
 
-    if args.copy_calibration:
-        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        b = torch.empty_like(a)
-        b.copy_(a)
-        torch.cuda.synchronize()
-        del a, b
+    copy_calibration(args, torch, dev)
 
     def step(r, events=None):
         if events is not None:

@@ -27,7 +27,7 @@ def gpu_quantize_fixed(B, x, delta, b, seed, rnd, worker, center=None):
 
 
 @pytest.mark.parametrize("b", [2, 4, 8, 16])
-@pytest.mark.parametrize("d", [1, 7, 8, 9, 31, 33, 511, 512, 513, 4099, 100_003, 1_000_000])
+@pytest.mark.parametrize("d", [1, 7, 8, 9, 31, 33, 511, 512, 513, 4095, 4096, 4097, 4099, 8192, 100_003, 1_000_000])
 def test_quantize_fixed_matches_oracle(oracle, B, b, d):
     g = torch.Generator(device="cpu").manual_seed(d + b)
     x = (torch.randn(d, generator=g) * 1e-3).to(torch.float32)
@@ -44,7 +44,45 @@ def test_quantize_fixed_matches_oracle(oracle, B, b, d):
     assert bad.size == 0, f"code words differ at {bad[:5]}"
 
 
-@pytest.mark.parametrize("b", [4, 8])
+def _steps_for_division():
+    one = np.float32(1.0)
+    out = [np.float32(2.0 ** -12), np.nextafter(np.float32(2.0 ** -10), np.float32(0)),      # significand all ones
+           np.nextafter(np.float32(2.0 ** -10), one), np.float32(3.0e-4), np.float32(1.0 / 3.0), np.float32(7.77e-7),
+           np.float32(2.0 ** -60), np.nextafter(np.float32(2.0 ** -60), np.float32(0)),      # both sides of the switch
+           np.float32(2.0 ** 60), np.nextafter(np.float32(2.0 ** 60), np.float32(np.inf)),
+           np.float32(1e-30), np.float32(1e30), np.float32(1e-38), np.float32(1e-41), np.float32(3e38)]
+    return [float(x) for x in out]
+
+
+@pytest.mark.parametrize("b", [2, 8, 16])
+@pytest.mark.parametrize("delta", _steps_for_division())
+def test_quantize_fixed_division_is_ieee_for_every_step(oracle, B, b, delta):
+    """The kernel divides by the step with a reciprocal computed once where that is exact and with
+    the full IEEE division elsewhere; the codes must equal the oracle's (which divides coordinate
+    by coordinate) for steps on both sides of the switch, steps whose significand is all ones, and
+    values from subnormal to far beyond the range."""
+    d = 1 << 19
+    g = torch.Generator(device="cpu").manual_seed(int(b * 1000 + abs(hash(delta)) % 997))
+    half = float(2 ** (b - 1))
+    u = torch.rand(d, generator=g, dtype=torch.float64) * 2 - 1
+    scale = torch.empty(d, dtype=torch.float64)
+    scale[0::4] = 1.0                                   # inside the range
+    scale[1::4] = 2.0 ** -20                            # near zero: floor 0 or -1
+    scale[2::4] = torch.pow(2.0, -(torch.rand(d // 4, generator=g, dtype=torch.float64) * 140))   # down to the subnormals of the quotient
+    scale[3::4] = torch.pow(2.0, torch.rand(d // 4, generator=g, dtype=torch.float64) * 100)      # far beyond the range
+    x64 = u * scale * half * delta
+    x = x64.clamp(-3.0e38, 3.0e38).to(torch.float32)
+    x[7] = 0.0
+    x[15] = -0.0
+    x[23] = 1e-45
+    x[31] = -1e-45
+    _, got = gpu_quantize_fixed(B, x.cuda(), delta, b, 31337, 1, 2)
+    want = oracle.quantize_fixed(x.numpy(), delta, b, 31337, 1, 2)
+    bad = np.nonzero(got != want)[0]
+    assert bad.size == 0, f"delta={delta!r}: code words differ at {bad[:5]}"
+
+
+@pytest.mark.parametrize("b", [2, 4, 8, 16])
 def test_quantize_fixed_with_center_and_grid_values(oracle, B, b):
     d = 50_001
     g = torch.Generator(device="cpu").manual_seed(b)
