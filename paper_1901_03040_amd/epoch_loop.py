@@ -28,6 +28,7 @@ class QesgdEpochLoop:
         self.z = torch.zeros_like(w0)
         self.u = w0.clone()
         self.zsum = torch.zeros_like(w0)
+        self.step = torch.zeros_like(w0)   # mean of the workers' quantised steps (gradient_round)
         self.round_id = 0          # global round counter: a new set of variates every round
         self.steps_in_epoch = 0
         self.lay = B.qesgd_layout_query(self.d, s, bucket)
@@ -58,6 +59,21 @@ class QesgdEpochLoop:
                                       self.packed.stride(0), self.ws)
         B.qesgd_unpack_aggregate_update(self.packed, self.packed.stride(0), self.K, self.d, self.s, self.bucket,
                                         self.w, self.z, self.u, self._zsum_arg(last))
+        self.round_id += 1
+        self.steps_in_epoch += 1
+        return self.u
+
+    def gradient_round(self, step_slab: torch.Tensor, last: bool = False) -> torch.Tensor:
+        """Gradient-compression baseline (QSGD as compared in Sec. 5): row k of step_slab is worker
+        k's -eta * g_k, quantised with the scale of what is sent (per bucket, or one scale over the
+        whole vector when bucket >= d).  z <- z + (1/K) sum_k Q(-eta g_k), u <- w_t + z.  Returns u."""
+        assert step_slab.shape[0] == self.K and step_slab.stride(0) % 4 == 0
+        B.qesgd_quantize_pack_batched(step_slab, step_slab.stride(0), None, self.d, self.s, self.bucket,
+                                      B.NORM_L2, self.seed, self.round_id, self.K, self.packed,
+                                      self.packed.stride(0), self.ws)
+        B.qesgd_unpack_aggregate(self.packed, self.packed.stride(0), self.K, self.d, self.s, self.bucket, self.step)
+        B.qesgd_apply_update(self.z, self.step, self.z, None, self.d)              # z += mean step
+        B.qesgd_apply_update(self.w, self.z, self.u, self._zsum_arg(last), self.d)  # u = w_t + z, zsum += z
         self.round_id += 1
         self.steps_in_epoch += 1
         return self.u
