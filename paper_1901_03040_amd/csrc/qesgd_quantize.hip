@@ -677,16 +677,17 @@ __global__ void k_tile_partials(const QParams p) {
 
 // Finishes the tree of one bucket: P leaves (a power of two, >= 16), of which only the first
 // `valid` were written (the rest of the padded bucket is +0, the identity of both combines, and is
-// never read).  One workgroup of 16 waves per (worker, bucket) walks the leaves in tiles of 16384
-// = 16 waves x 2 chunks x 512, each reduced like a tile of the first pass (leaf index bits 0-2 in
-// the lane, 3-8 across lanes, 9 across the two chunks, 10-13 across waves); the tile totals are
-// joined by a binary counter: stack[l] holds the finished subtree of 2^l tiles that waits for its
-// right sibling.
-constexpr uint32_t kFinishTile = 16384;
+// never read).  One workgroup of W = 1..16 waves per (worker, bucket) walks the leaves in tiles of
+// W x 2 chunks x 512, each reduced like a tile of the first pass (leaf index bits 0-2 in the
+// lane, 3-8 across lanes, 9 across the two chunks, then the waves); the tile totals are joined by
+// a binary counter: stack[l] holds the finished subtree of 2^l tiles that waits for its right
+// sibling.  W is the largest power of two with W x 1024 <= max(P, 1024).
 template <int KIND>
 __global__ void __launch_bounds__(1024) k_finish_norms(const QParams p, uint64_t P, uint32_t dense) {
     __shared__ float sm[2][16];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t nwaves = blockDim.x >> 6;
+    const uint64_t tile = (uint64_t)nwaves * 1024u;
     const uint64_t kb = blockIdx.x;                     // k*nb + b
     const uint32_t k = (uint32_t)(kb / p.nb);
     const uint64_t b = kb - (uint64_t)k * p.nb;
@@ -696,13 +697,13 @@ __global__ void __launch_bounds__(1024) k_finish_norms(const QParams p, uint64_t
         const uint64_t left = p.data_tiles - b * P;     // buckets before the last are full
         valid = left < P ? left : P;
     }
-    const uint64_t iters = (P + kFinishTile - 1) / kFinishTile;          // a power of two
+    const uint64_t iters = (P + tile - 1) / tile;                         // a power of two
     float stack[16];
 #pragma unroll
     for (int l = 0; l < 16; ++l) stack[l] = 0.0f;
     for (uint64_t it = 0; it < iters; ++it) {
         float total = 0.0f;
-        const uint64_t base = it * kFinishTile;
+        const uint64_t base = it * tile;
         if (base < valid) {                              // uniform: tiles beyond `valid` are all +0
             float t2[2];
 #pragma unroll
@@ -723,10 +724,10 @@ __global__ void __launch_bounds__(1024) k_finish_norms(const QParams p, uint64_t
             float* buf = sm[it & 1u];
             if (lane == 0) buf[wave] = combine<KIND>(t2[0], t2[1]);
             __syncthreads();                             // one barrier per tile: the buffers alternate
-            total = lds_tree16<KIND>(buf, 0, 16);
+            total = lds_tree16<KIND>(buf, 0, nwaves);
         }
 #pragma unroll
-        for (int l = 0; l < 16; ++l) {                   // iters <= 2^40 / 4096 / 16384 = 2^14
+        for (int l = 0; l < 16; ++l) {                   // 16 waves whenever P > 16384: iters <= 2^40 / 4096 / 16384 = 2^14
             if (((it >> l) & 1u) == 0u) { stack[l] = total; break; }
             total = combine<KIND>(stack[l], total);
         }
@@ -902,6 +903,9 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
         // bucket; then only the tiles that hold coordinates are visited, and the ones wholly inside
         // the vector take the unguarded kernels.
         const uint64_t P = sh.N / kPartialTile;          // tiles == nb * P
+        uint32_t finish_waves = 1;
+        while (finish_waves < 16 && (uint64_t)finish_waves * 1024u < P) finish_waves <<= 1;
+        const dim3 finish_block(finish_waves * kWaveSize);
         const bool dense = sh.N == sh.B || sh.nb == 1;
         const uint64_t data_tiles = dense ? (sh.d + kPartialTile - 1) / kPartialTile : tiles;
         const uint64_t full_tiles = (dense && a.norm_kind == QESGD_NORM_L2) ? sh.d / kPartialTile : 0;
@@ -935,7 +939,7 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
                 const dim3 grid((uint32_t)(data_tiles * kg));
                 if (p.center) hipLaunchKernelGGL(k_tile_partials_fast<true>, grid, block, 0, a.stream, p);
                 else hipLaunchKernelGGL(k_tile_partials_fast<false>, grid, block, 0, a.stream, p);
-                hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_L2>, finish_grid, dim3(1024), 0, a.stream, p, P, 1u);
+                hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_L2>, finish_grid, finish_block, 0, a.stream, p, P, 1u);
                 rc = check_launch();
                 if (rc != QESGD_OK) return rc;
                 launch_pre_fast(p, sh.m, (uint32_t)(data_tiles * kg), a.stream);
@@ -943,10 +947,10 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
                 const dim3 grid((uint32_t)(data_tiles * kg));
                 if (a.norm_kind == QESGD_NORM_L2) {
                     hipLaunchKernelGGL(k_tile_partials<QESGD_NORM_L2>, grid, block, 0, a.stream, p);
-                    hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_L2>, finish_grid, dim3(1024), 0, a.stream, p, P, dense ? 1u : 0u);
+                    hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_L2>, finish_grid, finish_block, 0, a.stream, p, P, dense ? 1u : 0u);
                 } else {
                     hipLaunchKernelGGL(k_tile_partials<QESGD_NORM_MAX>, grid, block, 0, a.stream, p);
-                    hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_MAX>, finish_grid, dim3(1024), 0, a.stream, p, P, dense ? 1u : 0u);
+                    hipLaunchKernelGGL(k_finish_norms<QESGD_NORM_MAX>, finish_grid, finish_block, 0, a.stream, p, P, dense ? 1u : 0u);
                 }
                 rc = check_launch();
                 if (rc != QESGD_OK) return rc;
