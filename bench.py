@@ -249,6 +249,25 @@ def bench_ceilings(args, cfg, torch, B, synth, dev):
         out["ceilings"][name] = {"bytes": nbytes, "ms_median": round(med, 4), "ms_min": round(ms[0], 4),
                                  "GBps": round(nbytes / med / 1e6, 1),
                                  "frac_of_hbm_peak": round(nbytes / med / 1e6 / HBM_PEAK_GBPS, 4)}
+    if args.sweeps:
+        # Back-to-back read sweeps over buffers of growing size: what a re-read gains when the
+        # buffer still sits in the 256 MB memory-side cache (it does below that size).
+        out["resident_sweeps"] = {}
+        for mib in (32, 64, 128, 200, 256, 512, 1024, 4096):
+            n = mib * (1 << 20) // 4
+            a = torch.empty(n, dtype=torch.float32, device=dev).normal_()
+            sink = torch.empty(n, dtype=torch.float32, device=dev)       # never written for ordinary data
+            for _ in range(3):
+                probe(PROBE_READ, a, sink, None, None, None, n, stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(20):
+                probe(PROBE_READ, a, sink, None, None, None, n, stream)
+            e1.record(stream)
+            e1.synchronize()
+            ms = e0.elapsed_time(e1) / 20
+            out["resident_sweeps"][f"{mib}MiB"] = {"us_per_sweep": round(ms * 1e3, 1), "GBps": round(4 * n / ms / 1e6, 1)}
+            del a, sink
     print(json.dumps(out), flush=True)
 
 
@@ -273,6 +292,9 @@ def main():
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the benchmark, time plain streaming kernels with the hot kernels' "
                          "access mixes on the workload's footprint (practical HBM ceilings of this machine)")
+    ap.add_argument("--sweeps", action="store_true",
+                    help="with --ceilings: also time 20 back-to-back read sweeps over buffers of 32 MiB .. 4 GiB "
+                         "(reach of the memory-side cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-full", action="store_true",
                     help="time the CPU oracle on the whole workload instead of a 2^26-coordinate prefix "
