@@ -289,6 +289,8 @@ def main():
                          "fixed: the paper-literal fixed-grid quantiser (b = 8) + its fused inverse")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a HIP graph (adds graph_replay_ms_per_step)")
+    ap.add_argument("--one-call", action="store_true",
+                    help="also time the step through qesgd_round (a whole round in one call / one launch; adds one_call)")
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the benchmark, time plain streaming kernels with the hot kernels' "
                          "access mixes on the workload's footprint (practical HBM ceilings of this machine)")
@@ -441,6 +443,24 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         out["graph_replay_ms_per_step"] = round((time.perf_counter() - g0) * 1e3 / args.steps, 4)
+    if args.one_call:
+        # The same step through qesgd_round: one launch where the shape allows it (it writes the
+        # packed blocks but does not read them back: K*P bytes fewer than the two-call form).
+        def round_call(r):
+            B.qesgd_round(slab, slab.stride(0), center, cfg.d, cfg.s, cfg.bucket, norm_kind, cfg.seed, r, cfg.K,
+                          packed, packed.stride(0), w, zbar, u, zsum, workspace=ws, stream=stream)
+        for r in range(args.warmup):
+            round_call(r)
+        torch.cuda.synchronize()
+        o0 = time.perf_counter()
+        for r in range(args.steps):
+            round_call(args.warmup + r)
+        torch.cuda.synchronize()
+        oms = (time.perf_counter() - o0) * 1e3 / args.steps
+        moved = qb + ub - cfg.K * lay.payload_bytes
+        out["one_call"] = {"ms_per_step": round(oms, 4), "bytes_moved": moved,
+                           "GBps_of_bytes_moved": round(moved / oms / 1e6, 1),
+                           "GBps_by_the_two_call_accounting": round((qb + ub) / oms / 1e6, 1)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, slab, w, lay, center=args.center, norm_kind=norm_kind,
                                            budget_elems=None if args.cpu_full else 1 << 26)

@@ -175,6 +175,20 @@ int qesgd_unpack_aggregate_update(const void* packed_slab, uint64_t packed_strid
                                   const float* w_snap, float* zbar_out, float* u_out,
                                   float* zsum_inout, void* stream);
 
+/* A whole round on a GPU that holds the K workers and the server: qesgd_quantize_pack_batched
+ * followed by qesgd_unpack_aggregate_update, same arguments, same results bit for bit (the packed
+ * blocks are written too).  Buckets are independent on the worker side (Sec. 3) and coordinates
+ * on the server side (Alg. 3, server task), so one workgroup can own one tile of every worker and
+ * of z: for a power-of-two bucket of 32..32768 coordinates, the L2 scale and a level width that
+ * divides 32 the round is a single launch that never reads the packed codes back; every other
+ * shape runs the two calls one after the other.  It exists for sizes at which a round is bound by
+ * its launches; in the method the two halves run on different machines. */
+int qesgd_round(const float* x_slab, uint64_t x_stride, const float* center,
+                uint64_t d, uint32_t s, uint64_t bucket, uint32_t norm_kind,
+                uint64_t seed, uint32_t round, uint32_t K,
+                void* packed_slab, uint64_t packed_stride, void* workspace, size_t workspace_bytes,
+                const float* w_snap, float* zbar_out, float* u_out, float* zsum_inout, void* stream);
+
 /* The quantiser exactly as the paper writes it (Sec. 2.1, Eq. (1)-(2)): fixed grid
  * {delta*k : -2^(b-1) <= k <= 2^(b-1)-1}, b in {2,4,8,16}, step delta chosen by the caller
  * (e.g. the schedule delta_t = O(1/(sqrt(t) 2^(b-1))) of Sec. 4).  Per coordinate:

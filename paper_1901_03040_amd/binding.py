@@ -83,6 +83,8 @@ def lib():
         L.qesgd_apply_update.restype = C.c_int
         L.qesgd_unpack_aggregate_update.argtypes = [vp, u64, u32, u64, u32, u64, vp, vp, vp, vp, vp]
         L.qesgd_unpack_aggregate_update.restype = C.c_int
+        L.qesgd_round.argtypes = [vp, u64, vp, u64, u32, u64, u32, u64, u32, u32, vp, u64, vp, sz, vp, vp, vp, vp, vp]
+        L.qesgd_round.restype = C.c_int
         L.qesgd_quantize_fixed.argtypes = [vp, vp, u64, C.c_float, u32, u64, u32, u32, vp, vp]
         L.qesgd_quantize_fixed.restype = C.c_int
         L.qesgd_dequantize_fixed_update.argtypes = [vp, u64, C.c_float, u32, vp, vp, vp, vp, vp]
@@ -173,6 +175,15 @@ def qesgd_unpack_aggregate_update(packed_slab, packed_stride, K, d, s, bucket, w
                                                int(s), int(bucket), _ptr(w_snap), _ptr(zbar_out),
                                                _ptr(u_out), _ptr(zsum_inout), _stream(stream)),
            "qesgd_unpack_aggregate_update")
+
+
+def qesgd_round(x_slab, x_stride, center, d, s, bucket, norm_kind, seed, rnd, K, packed_slab, packed_stride,
+                w_snap, zbar_out, u_out, zsum_inout, workspace=None, stream=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().qesgd_round(_ptr(x_slab), int(x_stride), _ptr(center), int(d), int(s), int(bucket), int(norm_kind),
+                             int(seed), int(rnd), int(K), _ptr(packed_slab), int(packed_stride), _ptr(workspace),
+                             ws_bytes, _ptr(w_snap), _ptr(zbar_out), _ptr(u_out), _ptr(zsum_inout), _stream(stream)),
+           "qesgd_round")
 
 
 def qesgd_quantize_fixed(x, center, d, delta, b, seed, rnd, worker, codes, stream=None):

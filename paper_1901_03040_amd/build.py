@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqesgd.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["qesgd_api.cpp", "qesgd_quantize.hip", "qesgd_aggregate.hip", "qesgd_fixed.hip"]
+SOURCES = ["qesgd_api.cpp", "qesgd_quantize.hip", "qesgd_aggregate.hip", "qesgd_fixed.hip", "qesgd_round.hip"]
 PROBE_SRC = "bench_probe.hip"
 PROBE_LIB = os.path.join(HERE, "libqesgd_bench_probe.so")
 

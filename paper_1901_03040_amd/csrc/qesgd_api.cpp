@@ -64,13 +64,14 @@ static size_t workspace_floats(const Shape& sh, uint32_t K) {
     return (size_t)K * sh.nb * (sh.N / kPartialTile);
 }
 
-static int quantize_common(const float* x, uint64_t x_stride, const float* center, uint64_t d,
-                           uint32_t s, uint64_t bucket, uint32_t norm_kind, uint64_t seed,
-                           uint32_t round, uint32_t worker0, uint32_t K, void* packed,
-                           uint64_t packed_stride, void* workspace, size_t workspace_bytes,
-                           void* stream, bool static_workspace = false) {
+// Validates a quantise call and fills the shape and the launch arguments; launches nothing.
+static int quantize_check(const float* x, uint64_t x_stride, const float* center, uint64_t d,
+                          uint32_t s, uint64_t bucket, uint32_t norm_kind, uint64_t seed,
+                          uint32_t round, uint32_t worker0, uint32_t K, void* packed,
+                          uint64_t packed_stride, void* workspace, size_t workspace_bytes,
+                          void* stream, bool static_workspace, Shape* shape, QuantizeArgs* args) {
     if (!x || !packed) return QESGD_ERR_NULL;
-    Shape sh;
+    Shape& sh = *shape;
     const int rc = make_shape(d, s, bucket, &sh);
     if (rc != QESGD_OK) return rc;
     if (K == 0 || K > QESGD_MAX_WORKERS) return QESGD_ERR_WORKERS;
@@ -93,7 +94,8 @@ static int quantize_common(const float* x, uint64_t x_stride, const float* cente
     } else if (need > 0 && (!workspace || workspace_bytes < need)) {
         return QESGD_ERR_WORKSPACE;
     }
-    QuantizeArgs a{};
+    QuantizeArgs& a = *args;
+    a = QuantizeArgs{};
     a.x = x;
     a.x_stride = x_stride;
     a.center = center;
@@ -106,22 +108,35 @@ static int quantize_common(const float* x, uint64_t x_stride, const float* cente
     a.packed_stride = packed_stride;
     a.workspace = (float*)workspace;
     a.stream = (hipStream_t)stream;
-    return launch_quantize(sh, a);
+    return QESGD_OK;
 }
 
-static int aggregate_common(const void* packed, uint64_t packed_stride, uint32_t K, uint64_t d,
-                            uint32_t s, uint64_t bucket, const float* w, float* zbar, float* u,
-                            float* zsum, bool fused, void* stream) {
+static int quantize_common(const float* x, uint64_t x_stride, const float* center, uint64_t d,
+                           uint32_t s, uint64_t bucket, uint32_t norm_kind, uint64_t seed,
+                           uint32_t round, uint32_t worker0, uint32_t K, void* packed,
+                           uint64_t packed_stride, void* workspace, size_t workspace_bytes,
+                           void* stream, bool static_workspace = false) {
+    Shape sh;
+    QuantizeArgs a;
+    const int rc = quantize_check(x, x_stride, center, d, s, bucket, norm_kind, seed, round, worker0, K, packed,
+                                  packed_stride, workspace, workspace_bytes, stream, static_workspace, &sh, &a);
+    return rc != QESGD_OK ? rc : launch_quantize(sh, a);
+}
+
+static int aggregate_check(const void* packed, uint64_t packed_stride, uint32_t K, uint64_t d,
+                           uint32_t s, uint64_t bucket, const float* w, float* zbar, float* u,
+                           float* zsum, bool fused, void* stream, Shape* shape, AggregateArgs* args) {
     if (!packed) return QESGD_ERR_NULL;
     if (fused ? (!w || !u) : !zbar) return QESGD_ERR_NULL;
-    Shape sh;
+    Shape& sh = *shape;
     const int rc = make_shape(d, s, bucket, &sh);
     if (rc != QESGD_OK) return rc;
     if (K == 0 || K > QESGD_MAX_WORKERS) return QESGD_ERR_WORKERS;
     if (!aligned(packed, 256) || !aligned(w, 16) || !aligned(zbar, 16) || !aligned(u, 16) || !aligned(zsum, 16))
         return QESGD_ERR_ALIGN;
     if (K > 1 && (packed_stride < sh.lay.bytes_per_worker || (packed_stride % 256) != 0)) return QESGD_ERR_STRIDE;
-    AggregateArgs a{};
+    AggregateArgs& a = *args;
+    a = AggregateArgs{};
     a.packed = (const unsigned char*)packed;
     a.packed_stride = packed_stride;
     a.K = K;
@@ -130,7 +145,16 @@ static int aggregate_common(const void* packed, uint64_t packed_stride, uint32_t
     a.u_out = u;
     a.zsum = zsum;
     a.stream = (hipStream_t)stream;
-    return launch_aggregate(sh, a);
+    return QESGD_OK;
+}
+
+static int aggregate_common(const void* packed, uint64_t packed_stride, uint32_t K, uint64_t d,
+                            uint32_t s, uint64_t bucket, const float* w, float* zbar, float* u,
+                            float* zsum, bool fused, void* stream) {
+    Shape sh;
+    AggregateArgs a;
+    const int rc = aggregate_check(packed, packed_stride, K, d, s, bucket, w, zbar, u, zsum, fused, stream, &sh, &a);
+    return rc != QESGD_OK ? rc : launch_aggregate(sh, a);
 }
 
 }  // namespace qesgd
@@ -198,6 +222,24 @@ int qesgd_unpack_aggregate_update(const void* packed_slab, uint64_t packed_strid
                                   float* zbar_out, float* u_out, float* zsum_inout, void* stream) {
     return aggregate_common(packed_slab, packed_stride, K, d, s, bucket, w_snap, zbar_out, u_out,
                             zsum_inout, true, stream);
+}
+
+int qesgd_round(const float* x_slab, uint64_t x_stride, const float* center, uint64_t d, uint32_t s,
+                uint64_t bucket, uint32_t norm_kind, uint64_t seed, uint32_t round, uint32_t K,
+                void* packed_slab, uint64_t packed_stride, void* workspace, size_t workspace_bytes,
+                const float* w_snap, float* zbar_out, float* u_out, float* zsum_inout, void* stream) {
+    Shape sh, sh2;
+    QuantizeArgs q;
+    AggregateArgs g;
+    int rc = quantize_check(x_slab, x_stride, center, d, s, bucket, norm_kind, seed, round, 0, K, packed_slab,
+                            packed_stride, workspace, workspace_bytes, stream, false, &sh, &q);
+    if (rc != QESGD_OK) return rc;
+    rc = aggregate_check(packed_slab, packed_stride, K, d, s, bucket, w_snap, zbar_out, u_out, zsum_inout, true,
+                         stream, &sh2, &g);
+    if (rc != QESGD_OK) return rc;
+    if (round_fused_covers(sh, norm_kind)) return launch_round_fused(sh, q, g);
+    rc = launch_quantize(sh, q);
+    return rc != QESGD_OK ? rc : launch_aggregate(sh, g);
 }
 
 static bool fixed_bits_ok(uint32_t b) { return b == 2 || b == 4 || b == 8 || b == 16; }

@@ -70,6 +70,10 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a);
 // Device address of the current GPU's static scratch (kStaticScratchFloats floats).
 int static_scratch(float** out);
 int launch_aggregate(const Shape& sh, const AggregateArgs& a);
+// One launch for a whole round (quantise K workers, sum, update) where the shape allows it:
+// power-of-two bucket of 32..32768 coordinates, L2 scale, level width dividing 32.
+bool round_fused_covers(const Shape& sh, uint32_t norm_kind);
+int launch_round_fused(const Shape& sh, const QuantizeArgs& a, const AggregateArgs& g);
 int launch_apply_update(const float* w, const float* zbar, float* u, float* zsum, uint64_t d,
                         hipStream_t stream);
 

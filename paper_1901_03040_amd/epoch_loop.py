@@ -54,11 +54,10 @@ class QesgdEpochLoop:
         """Compress-on-push round: row k of z_hat_slab is worker k's z - eta * g_k.
         z <- (1/K) sum_k Q(z_hat_k), u <- w_t + z.  Returns u."""
         assert z_hat_slab.shape[0] == self.K and z_hat_slab.stride(0) % 4 == 0
-        B.qesgd_quantize_pack_batched(z_hat_slab, z_hat_slab.stride(0), None, self.d, self.s, self.bucket,
-                                      B.NORM_L2, self.seed, self.round_id, self.K, self.packed,
-                                      self.packed.stride(0), self.ws)
-        B.qesgd_unpack_aggregate_update(self.packed, self.packed.stride(0), self.K, self.d, self.s, self.bucket,
-                                        self.w, self.z, self.u, self._zsum_arg(last))
+        # both halves of the round in one call (one launch for power-of-two buckets)
+        B.qesgd_round(z_hat_slab, z_hat_slab.stride(0), None, self.d, self.s, self.bucket, B.NORM_L2, self.seed,
+                      self.round_id, self.K, self.packed, self.packed.stride(0), self.w, self.z, self.u,
+                      self._zsum_arg(last), workspace=self.ws)
         self.round_id += 1
         self.steps_in_epoch += 1
         return self.u

@@ -127,6 +127,19 @@ def test_noalloc_argument_errors(B):
     assert "scratch" in B.strerror(B.ERR_SCRATCH)
 
 
+def test_round_argument_errors(B):
+    L = B.lib()
+    x, pk, w, z, u = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000
+    f = L.qesgd_round
+    assert f(None, 4096, None, 4096, 4, 512, 0, 1, 0, 2, pk, 1 << 20, None, 0, w, z, u, None, None) == B.ERR_NULL
+    assert f(x, 4096, None, 4096, 4, 512, 0, 1, 0, 2, pk, 1 << 20, None, 0, None, z, u, None, None) == B.ERR_NULL
+    assert f(x, 4096, None, 4096, 4, 512, 0, 1, 0, 0, pk, 1 << 20, None, 0, w, z, u, None, None) == B.ERR_WORKERS
+    assert f(x, 4096, None, 4096, 3, 512, 0, 1, 0, 2, pk, 1 << 20, None, 0, w, z, u, None, None) == B.ERR_LEVELS
+    assert f(x, 4000, None, 4096, 4, 512, 0, 1, 0, 2, pk, 1 << 20, None, 0, w, z, u, None, None) == B.ERR_STRIDE
+    assert f(x, 100_000, None, 100_000, 4, 100_000, 0, 1, 0, 2, pk, 1 << 20, None, 0, w, z, u, None, None) == B.ERR_WORKSPACE
+    assert f(x, 4096, None, 4096, 4, 512, 0, 1, 0, 2, pk, 1 << 20, None, 0, w, z, u + 4, None, None) == B.ERR_ALIGN
+
+
 def test_aggregate_argument_errors(B):
     L = B.lib()
     pk, z, w, u = 0x20000, 0x30000, 0x40000, 0x50000

@@ -84,6 +84,8 @@ static int launches = 0;
 int launch_quantize(const Shape&, const QuantizeArgs&) { ++launches; return QESGD_OK; }
 int static_scratch(float** out) { static float dummy[4]; *out = dummy; return QESGD_OK; }
 int launch_aggregate(const Shape&, const AggregateArgs&) { ++launches; return QESGD_OK; }
+bool round_fused_covers(const Shape& sh, uint32_t) { return sh.N == sh.B; }
+int launch_round_fused(const Shape&, const QuantizeArgs&, const AggregateArgs&) { ++launches; return QESGD_OK; }
 int launch_apply_update(const float*, const float*, float*, float*, uint64_t, hipStream_t) { ++launches; return QESGD_OK; }
 int launch_quantize_fixed(const float*, const float*, uint64_t, float, uint32_t, uint64_t, uint32_t, uint32_t, void*, hipStream_t) { ++launches; return QESGD_OK; }
 int launch_dequantize_fixed_update(const void*, uint64_t, float, uint32_t, const float*, float*, float*, float*, hipStream_t) { ++launches; return QESGD_OK; }
@@ -109,7 +111,10 @@ int main() {
     if (qesgd_quantize_pack_batched(x, 4096, nullptr, 4096, 4, 512, 0, 1, 0, 64, pk, 1 << 20, nullptr, 0, nullptr) != QESGD_OK) return 6;
     if (qesgd_quantize_pack_batched_noalloc(x, 1 << 20, nullptr, 1 << 20, 4, 1 << 20, 0, 1, 0, 3, pk, 1 << 22, nullptr) != QESGD_OK) return 7;
     if (qesgd_unpack_aggregate_update(pk, 1 << 20, 2, 4096, 4, 512, x, z, z, nullptr, nullptr) != QESGD_OK) return 8;
+    if (qesgd_round(x, 4096, nullptr, 4096, 4, 512, 0, 1, 0, 2, pk, 1 << 20, nullptr, 0, x, z, z, nullptr, nullptr) != QESGD_OK) return 17;
+    if (qesgd_round(x, 4096, nullptr, 4096, 4, 96, 0, 1, 0, 2, pk, 1 << 20, nullptr, 0, x, z, z, nullptr, nullptr) != QESGD_OK) return 18;
     const int before = qesgd::launches;
+    if (qesgd_round(x, 4096, nullptr, 4096, 4, 512, 0, 1, 0, 2, pk, 1 << 20, nullptr, 0, nullptr, z, z, nullptr, nullptr) != QESGD_ERR_NULL) return 19;
     if (qesgd_quantize_pack(x, nullptr, 0, 4, 512, 0, 1, 0, 0, pk, nullptr, 0, nullptr) != QESGD_ERR_DIM) return 9;
     if (qesgd_quantize_pack(x, nullptr, 1ull << 40, 4, 512, 0, 1, 0, 0, pk, nullptr, 0, nullptr) != QESGD_ERR_DIM) return 10;
     if (qesgd_quantize_pack(x, nullptr, 100000, 4, 100000, 0, 1, 0, 0, pk, nullptr, 0, nullptr) != QESGD_ERR_WORKSPACE) return 11;
