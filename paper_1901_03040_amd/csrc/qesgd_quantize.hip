@@ -109,6 +109,67 @@ __global__ void __launch_bounds__(Geo<LOG2N>::NW * 64) k_quantize_pack_fast(cons
     process_tile<M, LOG2N>(cx, buf, t, sm);
 }
 
+// The center form for several workers: a workgroup owns one tile of every worker, keeps the tile
+// of `center` in registers and takes the workers one after the other with the next worker's loads
+// in flight, so `center` is read once per tile instead of once per tile and worker.
+template <int M, int LOG2N>
+__global__ void __launch_bounds__(Geo<LOG2N>::NW * 64) k_quantize_pack_center(const QParams p) {
+    constexpr int CH = Geo<LOG2N>::CH;
+    constexpr uint32_t TILE = Geo<LOG2N>::TILE;
+    __shared__ float sm[2][32];             // alternate per worker: one barrier per tile suffices
+    const uint32_t t = blockIdx.x;
+    const uint32_t K = p.group_workers;
+    if (t >= p.full_tiles) {                              // the ragged last tile
+        for (uint32_t k = 0; k < K; ++k) guarded_tile<M, CH, QESGD_NORM_L2, false>(p, k, t, sm[k & 1u]);
+        return;
+    }
+    FastCtx cx;
+    cx.lane = threadIdx.x & 63u;
+    cx.wave = threadIdx.x >> 6;
+    cx.lane_off = cx.wave * (uint32_t)(CH * kChunk) + cx.lane * kLaneElems;
+    cx.round = p.round;
+    cx.key0 = p.key0;
+    cx.key1 = p.key1;
+    cx.smax = p.smax;
+    const uint64_t e0 = (uint64_t)t * TILE;
+    float4 ca[CH], cb[CH], a[CH], b[CH], na[CH], nb2[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const uint32_t o = cx.lane_off + (uint32_t)c * kChunk;
+        ca[c] = *reinterpret_cast<const float4*>(p.center + e0 + o);
+        cb[c] = *reinterpret_cast<const float4*>(p.center + e0 + o + 4);
+        a[c] = *reinterpret_cast<const float4*>(p.x + e0 + o);
+        b[c] = *reinterpret_cast<const float4*>(p.x + e0 + o + 4);
+    }
+    for (uint32_t k = 0; k < K; ++k) {
+        if (k + 1 < K) {
+            const float* __restrict__ xn = p.x + (uint64_t)(k + 1) * p.x_stride + e0;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const uint32_t o = cx.lane_off + (uint32_t)c * kChunk;
+                na[c] = *reinterpret_cast<const float4*>(xn + o);
+                nb2[c] = *reinterpret_cast<const float4*>(xn + o + 4);
+            }
+        }
+        float v[CH][8];
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            v[c][0] = a[c].x - ca[c].x; v[c][1] = a[c].y - ca[c].y; v[c][2] = a[c].z - ca[c].z; v[c][3] = a[c].w - ca[c].w;
+            v[c][4] = b[c].x - cb[c].x; v[c][5] = b[c].y - cb[c].y; v[c][6] = b[c].z - cb[c].z; v[c][7] = b[c].w - cb[c].w;
+        }
+        unsigned char* __restrict__ out = p.packed + (uint64_t)k * p.packed_stride;
+        cx.norms = reinterpret_cast<float*>(out + p.norms_off);
+        cx.signs = reinterpret_cast<uint32_t*>(out + p.signs_off);
+        cx.levels = reinterpret_cast<uint32_t*>(out + p.levels_off);
+        cx.worker = p.worker0 + k;
+        process_tile<M, LOG2N>(cx, v, t, sm[k & 1u]);
+        if (k + 1 < K) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) { a[c] = na[c]; b[c] = nb2[c]; }
+        }
+    }
+}
+
 // Tree sum (or max) of one 4096-slot tile of worker k with every access guarded per lane, left in
 // the workspace.  Tiles of a bucket are consecutive in slot space, so the workspace index of
 // (bucket, tile in bucket) is the tile index.  sm: 4 floats of LDS.
@@ -304,6 +365,13 @@ void launch_m(const QParams& p, uint32_t m, uint32_t norm_kind, dim3 grid, dim3 
 
 template <int M, int LOG2N>
 void launch_fast_one(const QParams& p, uint32_t blocks, hipStream_t st) {
+    // With a center and enough tiles to fill the chip many times over (measured: it pays from about
+    // 64 waves per SIMD on), a workgroup takes one tile of every worker and reads `center` once.
+    if (p.center && p.group_workers > 1 && (uint64_t)p.full_tiles * Geo<LOG2N>::NW >= 65536u) {
+        hipLaunchKernelGGL((k_quantize_pack_center<M, LOG2N>), dim3(p.full_tiles + p.tail_tiles),
+                           dim3(Geo<LOG2N>::NW * 64), 0, st, p);
+        return;
+    }
     if (p.center)
         hipLaunchKernelGGL((k_quantize_pack_fast<M, LOG2N, true>), dim3(blocks), dim3(Geo<LOG2N>::NW * 64), 0, st, p);
     else

@@ -81,6 +81,17 @@ def test_batched_with_center_tile_order(oracle, B, K, d, bucket, s):
                     center=c.cuda(), d=d)
 
 
+@pytest.mark.parametrize("d,bucket,s,K", [(4096 * 16400 + 77, 4096, 2, 2), (512 * 8 * 16390, 512, 16, 3)])
+def test_center_form_with_many_tiles(oracle, B, d, bucket, s, K):
+    """From 16384 tiles on, the center form lets one workgroup take a tile of every worker."""
+    g = torch.Generator(device="cuda").manual_seed(d % 1000 + K)
+    stride = (d + 63) // 64 * 64
+    c = torch.randn(d, generator=g, device="cuda")
+    slab = torch.zeros(K, stride, device="cuda")
+    slab[:, :d] = c[None, :] + torch.randn(K, d, generator=g, device="cuda") * 1e-3
+    run_and_compare(oracle, B, slab, s, bucket, 8, 2, K=K, center=c, d=d)
+
+
 def test_bench_probe_kernels_stay_in_their_buffers():
     """The benchmark's plain streaming kernels (their own shared object, not part of the library):
     copy and update mix give the expected values, the packed mixes write exactly the stated sizes,
