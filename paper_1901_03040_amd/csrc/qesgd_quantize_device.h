@@ -378,6 +378,9 @@ __device__ __forceinline__ void guarded_tile(const QParams& p, uint32_t k, uint3
 
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
+        // Lanes are in slot order, so a chunk whose first lane holds no coordinate is all padding
+        // (the tail of a bucket that is not a power of two, or of the vector): nothing to encode.
+        if (__builtin_amdgcn_readfirstlane(span[c].nvalid) == 0u) continue;
         const uint64_t g = span[c].i >> 3;
         uint32_t rnd[4];
         philox4x32_10((uint32_t)g, (uint32_t)(g >> 32), p.worker0 + k, p.round, p.key0, p.key1, rnd);

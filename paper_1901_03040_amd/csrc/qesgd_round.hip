@@ -41,6 +41,7 @@ __global__ void __launch_bounds__(Geo<LOG2N>::NW * 64) k_round_fused(const RPara
     constexpr int CH = Geo<LOG2N>::CH;
     constexpr uint32_t TILE = Geo<LOG2N>::TILE;
     __shared__ float sm[2][32];             // alternate per worker: one barrier per tile suffices
+    __shared__ float4 stage[Geo<LOG2N>::NW][128];
     const QParams& p = r.q;
     const uint32_t t = blockIdx.x;
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
@@ -94,9 +95,46 @@ __global__ void __launch_bounds__(Geo<LOG2N>::NW * 64) k_round_fused(const RPara
     }
 
     const float fk = (float)r.K;
+    if (t < p.full_tiles) {
+        // z moves from the lane-of-8 layout of the codes to one float4 of each 256-coordinate half
+        // per lane, so that every 128-bit access of a wave covers a contiguous KiB, through 2 KiB
+        // of LDS private to the wave (same wave on both sides: LDS keeps program order).
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            float z[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) z[e] = (r.rcpK != 0.0f) ? acc[c][e] * r.rcpK : acc[c][e] / fk;
+            stage[wave][2 * lane] = make_float4(z[0], z[1], z[2], z[3]);
+            stage[wave][2 * lane + 1] = make_float4(z[4], z[5], z[6], z[7]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const float4 za = stage[wave][lane];
+            const float4 zb = stage[wave][64 + lane];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();                       // the next chunk overwrites the staging area
+            const uint64_t ia = (uint64_t)t * TILE + wave * (uint32_t)(CH * kChunk) + (uint32_t)c * kChunk + lane * 4u;
+            const uint64_t ib = ia + 256u;
+            const float4 wa = *reinterpret_cast<const float4*>(r.w + ia);
+            const float4 wb = *reinterpret_cast<const float4*>(r.w + ib);
+            if (r.zbar) {
+                *reinterpret_cast<float4*>(r.zbar + ia) = za;
+                *reinterpret_cast<float4*>(r.zbar + ib) = zb;
+            }
+            *reinterpret_cast<float4*>(r.u + ia) = make_float4(wa.x + za.x, wa.y + za.y, wa.z + za.z, wa.w + za.w);
+            *reinterpret_cast<float4*>(r.u + ib) = make_float4(wb.x + zb.x, wb.y + zb.y, wb.z + zb.z, wb.w + zb.w);
+            if (r.zsum) {
+                const float4 sa = *reinterpret_cast<const float4*>(r.zsum + ia);
+                const float4 sb = *reinterpret_cast<const float4*>(r.zsum + ib);
+                *reinterpret_cast<float4*>(r.zsum + ia) = make_float4(sa.x + za.x, sa.y + za.y, sa.z + za.z, sa.w + za.w);
+                *reinterpret_cast<float4*>(r.zsum + ib) = make_float4(sb.x + zb.x, sb.y + zb.y, sb.z + zb.z, sb.w + zb.w);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-        // power-of-two buckets: slot == coordinate
+        // the ragged tile, lane by lane (power-of-two buckets: slot == coordinate)
         const uint64_t i = (uint64_t)t * TILE + lane_off + (uint32_t)c * kChunk;
         if (i >= p.d) continue;
         const uint64_t rem = p.d - i;
