@@ -84,7 +84,7 @@ def quantize_kernels(cfg, args, workspace_bytes):
         return "k_tile_partials(_fast) + k_finish_norms + k_quantize_pack_pre_fast (two passes, per group of workers)"
     pow2 = B & (B - 1) == 0
     m = cfg.s.bit_length() - 1
-    if pow2 and B >= 32 and args.norm == "l2" and 32 % m == 0 and cfg.d >= max(4096, B):
+    if pow2 and B >= 32 and args.norm == "l2" and 32 % m == 0:
         return "k_quantize_pack_fast"
     return "k_quantize_pack"
 

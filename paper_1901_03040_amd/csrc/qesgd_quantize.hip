@@ -489,8 +489,15 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
 
     const uint64_t slots = sh.nb * sh.N;                 // slot space of one worker
     const bool two_pass = sh.N > kMaxSinglePassBucket;
-    uint32_t ch = 2, nwaves = 4;                         // the same geometry as Geo<log2N>
-    if (!two_pass) {
+    // Tiles that lie wholly inside the vector go to the fast kernel when the bucket is a
+    // power of two (slot == coordinate), the scale is the L2 norm and the level width
+    // divides a word (the other widths are served by the generic kernel alone).
+    const bool fast = !two_pass && a.norm_kind == QESGD_NORM_L2 && sh.N == sh.B && sh.log2N >= 5 &&
+                      32u % sh.m == 0u;
+    uint32_t ch = 2, nwaves = 4;                         // generic kernel: 2 chunks per wave, 4..16 waves
+    if (fast) {
+        fast_geometry(sh.N, &ch, &nwaves);
+    } else if (!two_pass) {
         if (sh.N == 8192) nwaves = 8;
         else if (sh.N == 16384) nwaves = 16;
         else if (sh.N == 32768) { ch = 4; nwaves = 16; }
@@ -564,14 +571,10 @@ int launch_quantize(const Shape& sh, const QuantizeArgs& a) {
         return QESGD_OK;
     }
 
-    // Tiles that lie wholly inside the vector go to the fast kernel when the bucket is a
-    // power of two (slot == coordinate), the scale is the L2 norm and the level width
-    // divides a word (the other widths are served by the generic kernel alone).
-    uint64_t full_tiles = 0;
-    if (a.norm_kind == QESGD_NORM_L2 && sh.N == sh.B && sh.log2N >= 5 && 32u % sh.m == 0u) full_tiles = sh.d / tile;
-    if (full_tiles > 0) {
-        p.full_tiles = (uint32_t)full_tiles;
-        p.tail_tiles = (uint32_t)(tiles - full_tiles);
+    if (fast) {
+        // full_tiles may be 0 (a vector shorter than a tile): the launch is then one guarded tile per worker
+        p.full_tiles = (uint32_t)(sh.d / tile);
+        p.tail_tiles = (uint32_t)(tiles - p.full_tiles);
         launch_fast(p, sh.m, (uint32_t)(tiles * a.K), a.stream);
         return check_launch();
     }

@@ -211,10 +211,8 @@ int launch_round_fused(const Shape& sh, const QuantizeArgs& a, const AggregateAr
     p.worker0 = a.worker0;
     p.smax = (float)(sh.s - 1);
     p.group_workers = a.K;
-    uint32_t ch = 2, nwaves = 4;                          // Geo<log2N>
-    if (sh.N == 8192) nwaves = 8;
-    else if (sh.N == 16384) nwaves = 16;
-    else if (sh.N == 32768) { ch = 4; nwaves = 16; }
+    uint32_t ch, nwaves;
+    fast_geometry(sh.N, &ch, &nwaves);
     const uint64_t tile = (uint64_t)nwaves * ch * kChunk;
     const uint64_t tiles = (sh.nb * sh.N + tile - 1) / tile;
     if (tiles >= (1ull << 31)) return QESGD_ERR_DIM;
