@@ -47,7 +47,7 @@ __global__ void __launch_bounds__(256) k_unpack_aggregate_update(const AParams p
     for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
 
     if (p.wave_uniform_bucket) {
-        const uint64_t b = p.log2B >= 0 ? (wave_base >> p.log2B) : (wave_base / p.B);
+        const uint64_t b = bucket_of(wave_base, p);
         float my_step = 0.0f;
         if (lane < p.K) {
             const float norm = reinterpret_cast<const float*>(p.packed + (uint64_t)lane * p.packed_stride + p.norms_off)[b];
@@ -76,8 +76,46 @@ __global__ void __launch_bounds__(256) k_unpack_aggregate_update(const AParams p
             const float step = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_step), k));
             accumulate8<M>(acc, sbyte, w, step);
         }
+    } else if (p.wave_two_buckets) {
+        // Buckets of at least 512 coordinates that do not line up with the waves: a wave touches at
+        // most two of them.  Lane k divides worker k's scale of the first, lane 32 + k of the second.
+        const uint64_t b0 = bucket_of(wave_base, p);
+        const uint64_t boundary = (b0 + 1) * p.B;           // first coordinate of the second bucket
+        float my_step = 0.0f;
+        const uint32_t kk = lane & 31u;
+        const uint64_t bb = b0 + (lane >> 5);
+        if (kk < p.K && bb * p.B < p.d) {
+            const float norm = reinterpret_cast<const float*>(p.packed + (uint64_t)kk * p.packed_stride + p.norms_off)[bb];
+            my_step = norm / p.smax;
+        }
+        const bool second = i >= boundary;
+        uint32_t k = 0;
+        for (; k + 4 <= p.K; k += 4) {                    // four workers' codes in flight at a time
+            uint32_t sbyte[4], w[4][4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const unsigned char* __restrict__ blk = p.packed + (uint64_t)(k + j) * p.packed_stride;
+                sbyte[j] = (blk + p.signs_off)[i >> 3];
+                load_level_bits<M>(reinterpret_cast<const uint32_t*>(blk + p.levels_off), i, 8u, p.level_words, w[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float s0 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_step), k + j));
+                const float s1 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_step), 32u + k + j));
+                accumulate8<M>(acc, sbyte[j], w[j], second ? s1 : s0);
+            }
+        }
+        for (; k < p.K; ++k) {
+            const unsigned char* __restrict__ blk = p.packed + (uint64_t)k * p.packed_stride;
+            const uint32_t sbyte = (blk + p.signs_off)[i >> 3];
+            uint32_t w[4];
+            load_level_bits<M>(reinterpret_cast<const uint32_t*>(blk + p.levels_off), i, 8u, p.level_words, w);
+            const float s0 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_step), k));
+            const float s1 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_step), 32u + k));
+            accumulate8<M>(acc, sbyte, w, second ? s1 : s0);
+        }
     } else {
-        const uint64_t b = p.log2B >= 0 ? (i >> p.log2B) : (i / p.B);
+        const uint64_t b = bucket_of(i, p);
 #pragma unroll 4
         for (uint32_t k = 0; k < p.K; ++k) {
             const unsigned char* __restrict__ blk = p.packed + (uint64_t)k * p.packed_stride;
@@ -181,6 +219,7 @@ int launch_aggregate(const Shape& sh, const AggregateArgs& a) {
     p.rcpK = ((a.K & (a.K - 1)) == 0) ? 1.0f / (float)a.K : 0.0f;
 
     p.wave_uniform_bucket = (sh.B % kChunk == 0 || sh.nb == 1) ? 1u : 0u;
+    p.wave_two_buckets = (!p.wave_uniform_bucket && sh.B >= kChunk && a.K <= 32u) ? 1u : 0u;
 
     const uint64_t lanes = (sh.d + kLaneElems - 1) / kLaneElems;
     const uint64_t blocks = (lanes + 255) / 256;

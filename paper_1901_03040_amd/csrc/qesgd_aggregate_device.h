@@ -22,9 +22,21 @@ struct AParams {
     uint32_t K;
     int32_t log2B;          // >= 0 when B is a power of two, else -1
     uint32_t wave_uniform_bucket;   // 1 when every 512-aligned chunk lies inside one bucket
+    uint32_t wave_two_buckets;      // else 1 when a 512-aligned chunk touches at most two buckets and K <= 32
     float smax;
     float rcpK;             // exact 1/K when K is a power of two, else 0
 };
+
+// Bucket of coordinate i (a multiple of 8).  Bucket sizes are multiples of 32 unless there is a
+// single bucket, so the quotient can be taken in units of 32 coordinates: a 32-bit division for
+// every vector below 2^37 coordinates instead of a 64-bit one (which costs more vector
+// instructions than the rest of a lane's work).
+__device__ __forceinline__ uint64_t bucket_of(uint64_t i, const AParams& p) {
+    if (p.log2B >= 0) return i >> p.log2B;
+    if (p.B >= p.d) return 0;
+    if ((p.d >> 37) == 0) return (uint32_t)(i >> 5) / (uint32_t)(p.B >> 5);
+    return i / p.B;
+}
 
 __device__ __forceinline__ void store8(float* __restrict__ dst, uint64_t i, uint32_t nvalid, const float (&r)[8]) {
     if (nvalid == 8) {
@@ -130,7 +142,7 @@ __device__ __forceinline__ void aggregate_lane_guarded(const AParams& p, uint64_
     if (i >= p.d) return;
     const uint64_t rem = p.d - i;
     const uint32_t nvalid = rem < 8 ? (uint32_t)rem : 8u;
-    const uint64_t b = p.log2B >= 0 ? (i >> p.log2B) : (i / p.B);
+    const uint64_t b = bucket_of(i, p);
 
     float acc[8];
 #pragma unroll

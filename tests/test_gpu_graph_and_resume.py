@@ -22,9 +22,17 @@ def S():
     return synth
 
 
-def test_round_replays_from_a_graph(B, S):
-    cfg = S.by_name("cfg2").scaled(d=300_003, K=4)
+@pytest.mark.parametrize("form", ["two_calls", "one_call", "noalloc_wide_bucket", "two_calls_wide_bucket"])
+def test_round_replays_from_a_graph(B, S, form):
+    """One round captured in a graph and replayed with eager work in between, in the two-call form,
+    through qesgd_round (one launch), and with a whole-vector scale (several launches per call)
+    through the entry point that takes no workspace and the one that does."""
+    wide = form.endswith("wide_bucket")
+    cfg = S.by_name("cfg2").scaled(d=300_003, K=4, bucket=(1 << 30) if wide else None)
     slab = S.worker_slab(cfg, "cuda")
+    wsb = B.qesgd_workspace_bytes(cfg.d, cfg.s, cfg.bucket, cfg.K)
+    assert (wsb > 0) == wide
+    ws = torch.empty(max(wsb, 4) // 4, device="cuda")
     w = S.snapshot(cfg, "cuda")
     lay = B.qesgd_layout_query(cfg.d, cfg.s, cfg.bucket)
 
@@ -32,16 +40,28 @@ def test_round_replays_from_a_graph(B, S):
         return (B.alloc_packed(lay, cfg.K).zero_(), torch.zeros(cfg.d, device="cuda"),
                 torch.zeros(cfg.d, device="cuda"), torch.zeros(cfg.d, device="cuda"))
 
-    def one_round(packed, zbar, u, zsum, rnd):
+    def reference_round(packed, zbar, u, zsum, rnd):
         B.qesgd_quantize_pack_batched(slab, slab.stride(0), None, cfg.d, cfg.s, cfg.bucket, 0, cfg.seed, rnd,
-                                      cfg.K, packed, packed.stride(0))
+                                      cfg.K, packed, packed.stride(0), ws if wide else None)
         B.qesgd_unpack_aggregate_update(packed, packed.stride(0), cfg.K, cfg.d, cfg.s, cfg.bucket, w, zbar, u, zsum)
+
+    def one_round(packed, zbar, u, zsum, rnd):
+        if form == "one_call":
+            B.qesgd_round(slab, slab.stride(0), None, cfg.d, cfg.s, cfg.bucket, 0, cfg.seed, rnd, cfg.K, packed,
+                          packed.stride(0), w, zbar, u, zsum)
+            return
+        if form == "noalloc_wide_bucket":
+            B.qesgd_quantize_pack_batched_noalloc(slab, slab.stride(0), None, cfg.d, cfg.s, cfg.bucket, 0, cfg.seed,
+                                                  rnd, cfg.K, packed, packed.stride(0))
+            B.qesgd_unpack_aggregate_update(packed, packed.stride(0), cfg.K, cfg.d, cfg.s, cfg.bucket, w, zbar, u, zsum)
+            return
+        reference_round(packed, zbar, u, zsum, rnd)
 
     # eager reference: the same round three times (zsum accumulates 1x, 2x, 3x)
     ep, ez, eu, es = buffers()
     eager = []
     for _ in range(3):
-        one_round(ep, ez, eu, es, 7)
+        reference_round(ep, ez, eu, es, 7)
         torch.cuda.synchronize()
         eager.append((ep.clone(), ez.clone(), eu.clone(), es.clone()))
 

@@ -293,6 +293,27 @@ def test_unpack_aggregate_update_matches_oracle(oracle, B, S, s, K, d, bucket):
     assert torch.equal(u3, u)
 
 
+@pytest.mark.parametrize("s,K", [(2, 8), (16, 3), (256, 16), (4, 32), (4, 33), (8, 5)])
+@pytest.mark.parametrize("d,bucket", [(50_000, 3008), (200_003, 48_000), (20_000, 544), (70_001, 512 + 32)])
+def test_aggregate_with_buckets_that_straddle_waves(oracle, B, S, s, K, d, bucket):
+    """Buckets of 512 coordinates or more that are not a multiple of 512: a wave of the aggregate
+    kernel touches two buckets and shares their scales across lanes (up to 32 workers)."""
+    lay, packed = random_packed(B, S, d, s, bucket, K, seed=s + K + bucket)
+    g = torch.Generator(device="cpu").manual_seed(d)
+    w = torch.randn(d, generator=g)
+    zsum0 = torch.randn(d, generator=g) * 1e-2
+    zbar = torch.full((d,), float("nan"), device="cuda")
+    u = torch.full((d,), float("nan"), device="cuda")
+    zsum = zsum0.cuda()
+    B.qesgd_unpack_aggregate_update(packed, packed.stride(0), K, d, s, bucket, w.cuda(), zbar, u, zsum)
+    torch.cuda.synchronize()
+    norms, sw, lw = oracle_planes(B, packed, lay, K)
+    ozbar = oracle.unpack_aggregate(norms, sw, lw, d, s, bucket)
+    ou, ozsum = oracle.apply_update(w.numpy(), ozbar, zsum0.numpy())
+    for got, want, what in [(zbar, ozbar, "zbar"), (u, ou, "u"), (zsum, ozsum, "zsum")]:
+        assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32)), f"{what} not bit-exact"
+
+
 def test_full_round_small(oracle, B, S):
     """quantize -> aggregate -> update for several rounds, each side on its own intermediates."""
     cfg = S.by_name("cfg3").scaled(d=41_034, K=4)
