@@ -192,3 +192,36 @@ def test_fixed_grid_and_epoch_commit_argument_errors(B):
     assert L.qesgd_epoch_commit(w, zs + 4, 3, 100, None) == B.ERR_ALIGN
     for code in (B.ERR_BITS, B.ERR_DELTA, B.ERR_ROUNDS):
         assert "unknown" not in B.strerror(code)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/qesgd.h compiles as C99 (no C++ in the boundary) and a C program links against the
+    library's host-only calls."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("gcc not available")
+    from paper_1901_03040_amd import binding
+    src = tmp_path / "use_header.c"
+    src.write_text("""
+#include "qesgd.h"
+#include <stdio.h>
+int main(void) {
+    qesgd_layout lay;
+    int rc = qesgd_layout_query(138357544ull, 2u, 4096ull, &lay);
+    if (rc != QESGD_OK || lay.payload_bytes != 34724508ull) return 1;
+    if (qesgd_quantize_pack(0, 0, 10, 4, 32, QESGD_NORM_L2, 1, 0, 0, 0, 0, 0, 0) != QESGD_ERR_NULL) return 2;
+    if (qesgd_abi_version() != QESGD_ABI_VERSION) return 3;
+    puts(qesgd_strerror(QESGD_ERR_SCRATCH));
+    return 0;
+}
+""")
+    exe = tmp_path / "use_header"
+    lib_dir = os.path.dirname(binding.LIB_PATH)
+    built = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", f"-I{os.path.join(ROOT, 'include')}",
+                            str(src), "-o", str(exe), f"-L{lib_dir}", "-lqesgd", f"-Wl,-rpath,{lib_dir}"],
+                           capture_output=True, text=True)
+    assert built.returncode == 0, built.stderr[-2000:]
+    run = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0, (run.returncode, run.stderr[-1000:])
+    assert "scratch" in run.stdout
