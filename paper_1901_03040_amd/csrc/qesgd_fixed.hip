@@ -120,17 +120,19 @@ __device__ __forceinline__ void fixed_chunk(const FParams& p, const Divider<EXAC
     }
 }
 
-// A workgroup owns a tile of 4 waves x kFixedChunks chunks x 512 coordinates; a lane owns 8
-// consecutive coordinates of each of its wave's chunks (two 128-bit loads, one Philox call).  All
-// loads of a tile are issued before the first variate is drawn.  Tiles wholly inside the vector run
-// without guards; the ragged last tile guards every access per lane.  (One chunk per wave measured
-// fastest: 0.150 ms at d = 138 M, b = 8, against 0.155 / 0.158 ms for two / four chunks, and 0.165 ms
-// or more for persistent workgroups that keep the next tile's loads in flight.)
+// A workgroup owns a tile of kFixedWaves waves x kFixedChunks chunks x 512 coordinates; a lane
+// owns 8 consecutive coordinates of each of its wave's chunks (two 128-bit loads, one Philox call).
+// All loads of a tile are issued before the first variate is drawn.  Tiles wholly inside the
+// vector run without guards; the ragged last tile guards every access per lane.  The waves share
+// nothing, and the smallest unit measured fastest: at d = 138 M, b = 8, one wave x one chunk 0.144 ms,
+// four waves x one chunk 0.148 ms, four waves x two / four chunks 0.155 / 0.158 ms, persistent
+// workgroups that keep the next tile's loads in flight 0.165 ms or more.
 constexpr int kFixedChunks = 1;
-constexpr uint32_t kFixedTile = 4u * kFixedChunks * kChunk;
+constexpr uint32_t kFixedWaves = 1;
+constexpr uint32_t kFixedTile = kFixedWaves * kFixedChunks * kChunk;
 
 template <int B, bool CENTER, bool EXACT_DIV>
-__global__ void __launch_bounds__(256) k_quantize_fixed(const FParams p) {
+__global__ void __launch_bounds__(kFixedWaves * 64) k_quantize_fixed(const FParams p) {
     constexpr int CH = kFixedChunks;
     const Divider<EXACT_DIV> div(p.delta, p.lo, p.hi);
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
@@ -294,7 +296,7 @@ int launch_quantize_fixed(const float* x, const float* center, uint64_t d, float
     const uint64_t blocks = (d + kFixedTile - 1) / kFixedTile;
     if (blocks >= (1ull << 31)) return QESGD_ERR_DIM;
     p.full_tiles = (uint32_t)(d / kFixedTile);
-    const dim3 grid((uint32_t)blocks), block(256);
+    const dim3 grid((uint32_t)blocks), block(kFixedWaves * 64);
     // the short division is used where its scaling-free form is exact (see Divider)
     const bool exact_div = !(delta >= 0x1p-60f && delta <= 0x1p60f);
 #define QESGD_LAUNCH_FIXED(BB)                                                                                      \
