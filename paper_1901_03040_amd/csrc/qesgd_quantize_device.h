@@ -397,17 +397,19 @@ __device__ __forceinline__ void guarded_tile(const QParams& p, uint32_t k, uint3
 template <int LOG2N>
 struct Geo {
     // Buckets up to 2048: one chunk per wave (2048-coordinate tiles measured faster than 4096: 80
-    // against 84 us at d = 11 M); 4096 / 8192: two chunks per wave (one chunk and twice the waves is
-    // as fast at 4096 and much slower at 8192: 0.46 against 0.38 ms at d = 25.6 M, K = 16).
+    // against 84 us at d = 11 M), and two waves instead of four up to 1024 (0.84 against 0.86 ms at
+    // d = 138 M, K = 8, bucket 512 or 1024; one wave is slower again); 4096 / 8192: two chunks per
+    // wave (one chunk and twice the waves is as fast at 4096 and much slower at 8192: 0.46 against
+    // 0.38 ms at d = 25.6 M, K = 16).
     static constexpr int CH = (LOG2N == 15) ? 4 : (LOG2N <= 11 ? 1 : 2);
-    static constexpr int NW = (LOG2N <= 12) ? 4 : (LOG2N == 13 ? 8 : 16);
+    static constexpr int NW = (LOG2N <= 10) ? 2 : ((LOG2N <= 12) ? 4 : (LOG2N == 13 ? 8 : 16));
     static constexpr uint32_t TILE = (uint32_t)NW * CH * kChunk;
 };
 
 // Geo<log2 N> for a run-time N (host side): chunks per wave and waves per workgroup.
 inline void fast_geometry(uint64_t N, uint32_t* ch, uint32_t* nwaves) {
     *ch = N == 32768 ? 4u : (N <= 2048 ? 1u : 2u);
-    *nwaves = N <= 4096 ? 4u : (N == 8192 ? 8u : 16u);
+    *nwaves = N <= 1024 ? 2u : (N <= 4096 ? 4u : (N == 8192 ? 8u : 16u));
 }
 
 template <int CH, bool CENTER>
