@@ -18,8 +18,9 @@ namespace {
 // LDS private to the wave.  UPDATE: w, u present.  When the bucket size is a multiple of 512
 // the whole wave shares a bucket: lane k divides worker k's scale once and the loop reads it
 // back as a scalar.
-// Waves per workgroup; the waves share nothing (1, 2, 4 and 8 measured within 1.5% of each other).
-constexpr uint32_t kAggWaves = 4;
+// Waves per workgroup; the waves share nothing.  Two measured 1-2% faster than four or eight at
+// d = 11 M .. 138 M (0.532 against 0.539 ms at d = 138 M, K = 8), one the same as two.
+constexpr uint32_t kAggWaves = 2;
 template <int M, bool UPDATE, bool ZSUM, bool ZBAR>
 __global__ void __launch_bounds__(kAggWaves * 64) k_unpack_aggregate_update(const AParams p) {
     __shared__ float4 stage[kAggWaves][128];
