@@ -43,6 +43,26 @@ def host_cpu():
     return {"model": model, "online_cpus": os.cpu_count()}
 
 
+class one_core:
+    """Pins the calling thread to one host core for the timed part of the CPU baseline (the oracle
+    is single-threaded; this keeps it from migrating), and restores the mask afterwards."""
+
+    def __enter__(self):
+        self.allowed, self.core = None, None
+        try:
+            self.allowed = os.sched_getaffinity(0)
+            self.core = sorted(self.allowed)[len(self.allowed) // 2]
+            os.sched_setaffinity(0, {self.core})
+        except (AttributeError, OSError):
+            self.allowed = None
+        return self
+
+    def __exit__(self, *exc):
+        if self.allowed:
+            os.sched_setaffinity(0, self.allowed)
+        return False
+
+
 def cpu_baseline(cfg, slab, w, lay, center=False, norm_kind=0, budget_elems=1 << 26):
     """The oracle as it stands, one host thread, on a bucket-aligned prefix of the same workload
     (the whole vector when the bucket is wider than the budget, or with budget_elems=None)."""
@@ -52,17 +72,19 @@ def cpu_baseline(cfg, slab, w, lay, center=False, norm_kind=0, budget_elems=1 <<
     ds = cfg.d if budget_elems is None else min(cfg.d, max(B, (budget_elems // B) * B))
     host = slab[:, :ds].cpu().numpy()
     wh = w[:ds].cpu().numpy()
-    t0 = time.perf_counter()
-    planes = [oracle.quantize_pack(host[k], cfg.s, cfg.bucket, cfg.seed, 0, k, center=wh if center else None,
-                                   norm_kind=norm_kind) for k in range(cfg.K)]
-    t1 = time.perf_counter()
-    norms = np.stack([p[0] for p in planes])
-    sw = np.stack([p[1] for p in planes])
-    lw = np.stack([p[2] for p in planes])
-    t2 = time.perf_counter()
-    zbar = oracle.unpack_aggregate(norms, sw, lw, ds, cfg.s, cfg.bucket)
-    oracle.apply_update(wh, zbar, np.zeros(ds, np.float32))
-    t3 = time.perf_counter()
+    with one_core() as pin:
+        t0 = time.perf_counter()
+        planes = [oracle.quantize_pack(host[k], cfg.s, cfg.bucket, cfg.seed, 0, k, center=wh if center else None,
+                                       norm_kind=norm_kind) for k in range(cfg.K)]
+        t1 = time.perf_counter()
+        norms = np.stack([p[0] for p in planes])
+        sw = np.stack([p[1] for p in planes])
+        lw = np.stack([p[2] for p in planes])
+        t2 = time.perf_counter()
+        zbar = oracle.unpack_aggregate(norms, sw, lw, ds, cfg.s, cfg.bucket)
+        oracle.apply_update(wh, zbar, np.zeros(ds, np.float32))
+        t3 = time.perf_counter()
+    pinned = pin.core
     nb, nsw, nlw, _, _ = oracle.shape(ds, cfg.s, cfg.bucket)
     P = 4 * (nb + nsw + nlw)
     qb, ub = cfg.K * (4 * ds + P) + (4 * ds if center else 0), cfg.K * P + 20 * ds
@@ -73,7 +95,7 @@ def cpu_baseline(cfg, slab, w, lay, center=False, norm_kind=0, budget_elems=1 <<
                   f"({cfg.K * ds} coordinate quantisations)",
         "quantize_GBps": round(qb / tq / 1e9, 4), "aggregate_update_GBps": round(ub / tu / 1e9, 4),
         "quantize_params_per_s": round(cfg.K * ds / tq), "aggregate_update_params_per_s": round(ds / tu),
-        "seconds": round(tq + tu, 2), "host": host_cpu(),
+        "seconds": round(tq + tu, 2), "host": host_cpu(), "pinned_to_core": pinned,
     }
 
 
@@ -174,11 +196,12 @@ def bench_fixed_grid(args, cfg, torch, B, synth, dev):
         from oracle import qesgd_oracle as oracle
         ds = min(d, 1 << 26)
         xh, wh = x[:ds].cpu().numpy(), w[:ds].cpu().numpy()
-        t0 = time.perf_counter()
-        oc = oracle.quantize_fixed(xh, delta, b, cfg.seed, 0, 0)
-        t1 = time.perf_counter()
-        oracle.dequantize_fixed_update(oc, ds, delta, b, w_snap=wh, zsum=np.zeros(ds, np.float32))
-        t2 = time.perf_counter()
+        with one_core():
+            t0 = time.perf_counter()
+            oc = oracle.quantize_fixed(xh, delta, b, cfg.seed, 0, 0)
+            t1 = time.perf_counter()
+            oracle.dequantize_fixed_update(oc, ds, delta, b, w_snap=wh, zsum=np.zeros(ds, np.float32))
+            t2 = time.perf_counter()
         sb = 4 * ds + ds + ds + 20 * ds
         out["cpu_baseline"] = {"value": round(sb / (t2 - t0) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
                                "sample": f"first {ds} of {d} coordinates, one step",
