@@ -68,7 +68,7 @@ enum {
     QESGD_OK = 0,
     QESGD_ERR_NULL = -1,       /* a required pointer is NULL                          */
     QESGD_ERR_DIM = -2,        /* d == 0 or d >= 2^40, or the launch would need 2^31
-                                  workgroups or more (one per 4096..65536 coordinates
+                                  workgroups or more (one per 1024..65536 coordinates
                                   and worker: e.g. d = 2^38 with K = 64)              */
     QESGD_ERR_LEVELS = -3,     /* s not 2,4,8,16,32,64,128,256 or 65536                */
     QESGD_ERR_BUCKET = -4,     /* bucket == 0, or bucket < d and bucket % 32 != 0      */
