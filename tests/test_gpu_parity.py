@@ -221,6 +221,40 @@ def test_wide_buckets_batched(oracle, B, d, bucket, s, K, norm_kind, with_center
         assert torch.equal(single[0], packed[k]), k
 
 
+@pytest.mark.parametrize("d,bucket,s,K,norm_kind,with_center", [
+    (6_000_037, 1 << 30, 2, 8, 0, False),     # one bucket over the vector: 8 x 24 MB of input, groups of 6 + 2 workers
+    (5_500_000, 65_536, 16, 9, 0, True),      # wide power-of-two buckets with a center: groups of 7 + 2
+    (5_300_011, 48_000, 256, 8, 1, False)])   # not a power of two, max norm (guarded passes): groups of 7 + 1
+def test_wide_buckets_input_beyond_one_group(oracle, B, d, bucket, s, K, norm_kind, with_center):
+    """The wide-bucket path takes the workers of a call in groups whose input stays within a fixed
+    byte budget (160 MB).  Here one call needs two groups: every scale and code word of every worker
+    against the oracle, so the per-group offsets of input, output, workspace and worker index are
+    all exercised; the entry point without a workspace gives the same bytes."""
+    g = torch.Generator(device="cpu").manual_seed(d + K)
+    stride = (d + 63) // 64 * 64
+    assert K * 4 * d > 160 << 20 and 4 * d < 160 << 20
+    slab = torch.zeros(K, stride)
+    slab[:, :d] = torch.randn(K, d, generator=g) * 1e-3 * (1 + torch.arange(K))[:, None]
+    c = (torch.randn(d, generator=g) * 1e-3) if with_center else None
+    lay = B.qesgd_layout_query(d, s, bucket)
+    wsb = B.qesgd_workspace_bytes(d, s, bucket, K)
+    assert 0 < wsb <= B.NOALLOC_SCRATCH_BYTES
+    ws = torch.full((wsb // 4,), float("nan"), device="cuda")
+    packed = B.alloc_packed(lay, K)
+    packed.fill_(0xA5)
+    dslab, dc = slab.cuda(), None if c is None else c.cuda()
+    B.qesgd_quantize_pack_batched(dslab, stride, dc, d, s, bucket, norm_kind, 77, 5, K, packed, packed.stride(0), ws)
+    torch.cuda.synchronize()
+    for k in range(K):
+        assert_codes_equal(oracle, B, slab[k, :d].numpy(), s, bucket, 77, 5, k, lay, packed[k],
+                           center_host=None if c is None else c.numpy(), norm_kind=norm_kind)
+    again = B.alloc_packed(lay, K)
+    again.fill_(0xA5)
+    B.qesgd_quantize_pack_batched_noalloc(dslab, stride, dc, d, s, bucket, norm_kind, 77, 5, K, again, again.stride(0))
+    torch.cuda.synchronize()
+    assert torch.equal(again, packed)
+
+
 @pytest.mark.parametrize("name,d", [("cfg1", 16_384), ("cfg2", 40_000), ("cfg3", 41_034), ("cfg4", 70_008),
                                     ("cfg5", 61_000)])
 def test_config_distributions_small(oracle, B, S, name, d):
