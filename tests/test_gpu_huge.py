@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import torch
 
-from test_gpu_parity import B, S, oracle_planes, random_packed  # noqa: F401
+from test_gpu_parity import B, S, assert_codes_equal, oracle_planes, random_packed  # noqa: F401
 
 pytestmark = pytest.mark.gpu
 
@@ -100,3 +100,30 @@ def test_beyond_2_to_35_coordinates_philox_counter_high_word(oracle, B):
     rng = np.random.default_rng(6)
     buckets = sorted({0, edge - 1, edge, edge + 2, nb - 2, nb - 1, *rng.integers(0, nb, size=4).tolist()})
     check_buckets(oracle, B, x, packed[0], lay, d, s, bucket, seed, rnd, worker, buckets)
+
+
+@pytest.mark.parametrize("d,bucket,s,K,norm_kind", [
+    (138_357_544, 1 << 30, 2, 2, 0),            # one bucket of 2^28 slots: 65,536 partial sums, 4 finish tiles
+    ((1 << 28) + 12_345, 1 << 27, 4, 1, 0),     # buckets of 2^27: two full ones and a short one
+    (70_000_003, 1 << 30, 16, 1, 1)])           # max norm over 2^27 slots (guarded passes)
+def test_buckets_beyond_one_finish_tile(oracle, B, d, bucket, s, K, norm_kind):
+    """Buckets with more partial sums (one per 4096 coordinates) than the 16,384 one workgroup of the
+    finishing pass reduces at a time: its per-tile totals are joined like the rest of the tree.
+    Every scale and code word against the oracle."""
+    need_free(8)
+    g = torch.Generator(device="cpu").manual_seed(d % 1000 + K)
+    stride = (d + 63) // 64 * 64
+    slab = torch.zeros(K, stride)
+    slab[:, :d] = torch.randn(K, d, generator=g) * 1e-3
+    slab[:, 12_345_678] = 0.75                      # one entry that dominates the max norm
+    lay = B.qesgd_layout_query(d, s, bucket)
+    wsb = B.qesgd_workspace_bytes(d, s, bucket, K)
+    assert wsb // 4 // K // lay.n_buckets > 16_384
+    ws = torch.full((wsb // 4,), float("nan"), device="cuda")
+    packed = B.alloc_packed(lay, K)
+    packed.fill_(0xA5)
+    B.qesgd_quantize_pack_batched(slab.cuda(), stride, None, d, s, bucket, norm_kind, 3, 1, K, packed,
+                                  packed.stride(0), ws)
+    torch.cuda.synchronize()
+    for k in range(K):
+        assert_codes_equal(oracle, B, slab[k, :d].numpy(), s, bucket, 3, 1, k, lay, packed[k], norm_kind=norm_kind)
